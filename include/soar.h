@@ -1,0 +1,193 @@
+/*
+ * soar.h -- C-ABI of the MI355X (gfx950) SOAR NVFP4 weight-quantization library.
+ *
+ * The library implements the data-parallel hot path of SOAR (arXiv 2605.12245):
+ * NVFP4 weight quantization (Sec. 3.1) with one Closed-form Joint Scale
+ * Optimization step (Sec. 3.2, Eq. 5-6) followed by one Decoupled Scale Search
+ * over E4M3 candidates for the stored block scale (Sec. 3.3, Eq. 7-8;
+ * Algorithm 1 with T = 1 and beta = 1).
+ *
+ * Conventions common to all entry points
+ *   - every pointer whose name starts with d_ is DEVICE memory owned by the
+ *     caller; the library allocates nothing persistent and frees nothing;
+ *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without synchronising; results
+ *     (global scale, error, data-dependent status) stay in device memory;
+ *   - weights are row-major, `rows x cols`, leading dimension `ld_elems` >= cols
+ *     (in elements); a block is 16 consecutive elements of a row, so
+ *     cols % 16 == 0 is required; the weight base address must be 16-byte
+ *     aligned and ld_elems * element size a multiple of 16 bytes;
+ *   - packed codes: rows*cols/2 bytes, row-major and dense; element 2k of a row
+ *     sits in bits 0-3 of byte k, element 2k+1 in bits 4-7; a nibble is
+ *     sign<<3 | E2M1 magnitude code, magnitudes {0,.5,1,1.5,2,3,4,6};
+ *   - block scales: rows*cols/16 bytes, row-major and dense, one positive OCP
+ *     E4M3 ("fn": bias 7, max 448) byte in [0x01, 0x7E] per block;
+ *   - host-checkable argument errors are returned before anything is enqueued
+ *     and leave every output untouched; no exception crosses this boundary.
+ */
+#ifndef SOAR_H
+#define SOAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SOAR_OK = 0,
+    SOAR_ERR_NULL = 1,       /* a required pointer is NULL                          */
+    SOAR_ERR_SHAPE = 2,      /* rows/cols/ld out of range, cols % 16 != 0           */
+    SOAR_ERR_DTYPE = 3,      /* unknown element type                                */
+    SOAR_ERR_PARAM = 4,      /* bad soar_params field                               */
+    SOAR_ERR_WORKSPACE = 5,  /* workspace missing, misaligned or too small          */
+    SOAR_ERR_HIP = 6,        /* a HIP runtime call failed (launch error)            */
+    SOAR_ERR_ALIGN = 7       /* weight/output pointer or leading dimension misaligned */
+} soar_status;
+
+typedef enum { SOAR_BF16 = 0, SOAR_FP32 = 1 } soar_dtype;
+
+typedef enum {
+    SOAR_METHOD_RTN = 0,     /* max-based NVFP4, Sec. 3.1 Eq. 1-2                   */
+    SOAR_METHOD_SOAR = 1     /* Eq. 1-2 init, Eq. 5-6 step, Eq. 8 search            */
+} soar_method;
+
+/* how the Eq. 8 search is carried out; every mode returns the same bytes */
+typedef enum {
+    SOAR_SEARCH_AUTO = 0,    /* the library's fastest exact strategy                */
+    SOAR_SEARCH_FULL = 1     /* evaluate all 2K+1 candidates                        */
+} soar_search_mode;
+
+/* data-dependent status bits written to *d_status */
+#define SOAR_STATUS_NONFINITE 1   /* NaN or Inf in the weights: outputs unspecified  */
+#define SOAR_STATUS_ALLZERO   2   /* every weight is zero                            */
+
+typedef struct {
+    uint32_t struct_size;    /* sizeof(soar_params), for forward compatibility      */
+    int32_t  method;         /* soar_method                                         */
+    int32_t  block;          /* block size G of Algorithm 1; must be 16             */
+    int32_t  iters;          /* iterations T of Algorithm 1; must be 1              */
+    int32_t  dss_radius;     /* K >= 0: stored-scale candidates are the E4M3 codes
+                                centre-K .. centre+K (Sec. 3.3 (ii)); 0 = centre only */
+    int32_t  n_beta;         /* size of the quantization-scale grid; must be 1      */
+    float    beta_lo;        /* must be 1                                           */
+    float    beta_hi;        /* must be 1                                           */
+    float    early_stop_rel; /* unused while iters == 1                             */
+    int32_t  search_mode;    /* soar_search_mode                                    */
+    int32_t  tiles_per_wg;   /* 0 = chosen by the library; a power of two <= 65536
+                                forces how many 256-block tiles one workgroup walks
+                                (for tests: outputs must not depend on it)          */
+} soar_params;
+
+/* Fills *p with the hot-path defaults: SOAR, block 16, T = 1, K = 4, beta = {1}. */
+void soar_default_params(soar_params *p);
+
+/*
+ * Bytes of device workspace soar_quantize needs for a rows x cols tensor
+ * (control words and per-workgroup partial sums of the tensor-wide reductions).
+ * The workspace must be 256-byte aligned; its contents need no initialisation
+ * and are undefined afterwards.  Returns 0 on a bad argument.
+ */
+size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params);
+
+/*
+ * soar_quantize -- the hot path.
+ *
+ * method RTN (Sec. 3.1): alpha = max|W| / (6*448); Delta_i = E4M3(max|W_i| /
+ * (6 alpha)) (Eq. 1); codes = Q_FP4(W / (alpha Delta)) (Eq. 2).
+ * method SOAR (Algorithm 1, T = 1): starts from the RTN state with
+ * Delta^q = Delta^d; alpha <- Eq. 5; Delta*_i <- Eq. 6, kept unrounded as the
+ * quantization scale Delta^q; codes <- Q_FP4(W / (alpha Delta^q)); the stored
+ * scale Delta^d is the E4M3 code among centre-K..centre+K (centre = E4M3
+ * projection of Delta*, Appendix D) that minimises the block error of Eq. 8,
+ * candidates being tried in the order 0,-1,+1,-2,+2,... and a later one winning
+ * only if strictly better in binary32.
+ *
+ * d_w            in   weights, bf16 or fp32 (see conventions)
+ * d_codes        out  rows*cols/2 bytes
+ * d_scales       out  rows*cols/16 bytes
+ * d_global_scale out  1 float: alpha (1.0 for an all-zero tensor)
+ * d_sse          out  1 double, may be NULL: sum over blocks of the Eq. 8 error
+ *                     of the emitted codes and scales (= Eq. 4)
+ * d_status       out  1 int32, may be NULL: SOAR_STATUS_* bits
+ * d_workspace    tmp  >= soar_workspace_bytes(), 256-byte aligned; calls that
+ *                     share a workspace must be ordered on one stream
+ */
+soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols,
+                          int64_t ld_elems, const soar_params *params,
+                          uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale,
+                          double *d_sse, int32_t *d_status,
+                          void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* One tensor of a batch: the arguments of soar_quantize that differ per tensor. */
+typedef struct {
+    const void *d_w;
+    int32_t     dtype;           /* soar_dtype */
+    int64_t     rows, cols, ld_elems;
+    uint8_t    *d_codes;
+    uint8_t    *d_scales;
+    float      *d_global_scale;
+    double     *d_sse;           /* may be NULL */
+    int32_t    *d_status;        /* may be NULL */
+} soar_tensor_desc;
+
+/*
+ * soar_quantize_batch -- soar_quantize for n tensors (the linear layers of a
+ * model, Sec. 4.1), enqueued back to back on one stream with one shared
+ * workspace of at least the largest soar_workspace_bytes() of its members.
+ * `descs` is HOST memory and is not referenced after the call returns.  All
+ * descriptors are validated before anything is enqueued.
+ */
+soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params,
+                                void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * soar_dequantize -- Eq. 3: w^_ij = q_ij * (alpha * d_i), the product alpha*d_i
+ * rounded to binary32 first; bf16 output rounds to nearest even.
+ * d_out: rows x cols with leading dimension ld_elems, 16-byte aligned.
+ */
+soar_status soar_dequantize(const uint8_t *d_codes, const uint8_t *d_scales,
+                            const float *d_global_scale, int64_t rows, int64_t cols,
+                            soar_dtype out_dtype, void *d_out, int64_t ld_elems, void *hip_stream);
+
+/*
+ * soar_recon_error -- Eq. 4: sum_ij (w_ij - q_ij * alpha * d_i)^2 for stored
+ * codes / scales / global scale, each block evaluated as in Eq. 8 (binary32),
+ * blocks accumulated in binary64.  *d_sse is overwritten.
+ */
+soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols,
+                             int64_t ld_elems, const uint8_t *d_codes, const uint8_t *d_scales,
+                             const float *d_global_scale, double *d_sse, void *hip_stream);
+
+/*
+ * Element-wise projections onto the two small formats, exposed so that the
+ * hardware conversion paths can be checked exhaustively (Sec. 3.1 Eq. 2;
+ * Appendix D last equation).  d_x: n floats.  d_out: n bytes -- an E2M1 nibble
+ * (sign<<3 | magnitude code, saturating, round to nearest even) or a clipped
+ * E4M3 code in [0x01, 0x7E].
+ */
+soar_status soar_e2m1_round_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream);
+soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel the library
+ * launches is bracketed by HIP events on its stream.  soar_kernel_timing_read
+ * synchronises, returns total milliseconds and launch count of one kernel
+ * family since the last reset, and soar_kernel_timing_enable(…) resets.
+ * Not thread-safe; leave disabled in production.
+ */
+typedef enum {
+    SOAR_KERNEL_INIT = 0, SOAR_KERNEL_ABSMAX = 1, SOAR_KERNEL_STATS = 2, SOAR_KERNEL_SEARCH = 3,
+    SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_COUNT = 6
+} soar_kernel_id;
+void        soar_kernel_timing_enable(int enable);
+soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches);
+
+const char *soar_status_string(soar_status s);
+uint32_t    soar_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOAR_H */

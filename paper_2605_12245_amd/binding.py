@@ -1,0 +1,258 @@
+"""ctypes view of the HIP library's C-ABI (``include/soar.h``).
+
+Argument marshalling only: every step of the method runs inside the HIP
+kernels.  torch is used for device memory and streams.  There is no CPU
+fallback -- if ``libsoar_hip.so`` has not been built, or no GPU is present,
+the entry points raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+SOAR_OK = 0
+SOAR_BF16, SOAR_FP32 = 0, 1
+SOAR_METHOD_RTN, SOAR_METHOD_SOAR = 0, 1
+SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
+SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO = 1, 2
+(SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
+ SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_COUNT) = range(7)
+
+EXPORTS = (
+    "soar_default_params", "soar_workspace_bytes", "soar_quantize", "soar_quantize_batch",
+    "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
+    "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
+)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsoar_hip.so")
+_lib = None
+
+
+class SoarError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().soar_status_string(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (status {code})")
+
+
+class soar_params(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("method", C.c_int32), ("block", C.c_int32),
+        ("iters", C.c_int32), ("dss_radius", C.c_int32), ("n_beta", C.c_int32),
+        ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
+        ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32),
+    ]
+
+
+class soar_tensor_desc(C.Structure):
+    _fields_ = [
+        ("d_w", C.c_void_p), ("dtype", C.c_int32),
+        ("rows", C.c_int64), ("cols", C.c_int64), ("ld_elems", C.c_int64),
+        ("d_codes", C.c_void_p), ("d_scales", C.c_void_p), ("d_global_scale", C.c_void_p),
+        ("d_sse", C.c_void_p), ("d_status", C.c_void_p),
+    ]
+
+
+def lib():
+    """Load the HIP library; raise loudly when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2605_12245_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    L.soar_default_params.argtypes = [C.POINTER(soar_params)]
+    L.soar_default_params.restype = None
+    L.soar_workspace_bytes.argtypes = [i64, i64, C.POINTER(soar_params)]
+    L.soar_workspace_bytes.restype = C.c_size_t
+    L.soar_quantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_params), vp, vp, vp, vp, vp,
+                                vp, C.c_size_t, vp]
+    L.soar_quantize.restype = i32
+    L.soar_quantize_batch.argtypes = [i32, C.POINTER(soar_tensor_desc), C.POINTER(soar_params), vp,
+                                      C.c_size_t, vp]
+    L.soar_quantize_batch.restype = i32
+    L.soar_dequantize.argtypes = [vp, vp, vp, i64, i64, i32, vp, i64, vp]
+    L.soar_dequantize.restype = i32
+    L.soar_recon_error.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
+    L.soar_recon_error.restype = i32
+    L.soar_e2m1_round_f32.argtypes = [vp, i64, vp, vp]
+    L.soar_e2m1_round_f32.restype = i32
+    L.soar_e4m3_project_f32.argtypes = [vp, i64, vp, vp]
+    L.soar_e4m3_project_f32.restype = i32
+    L.soar_kernel_timing_enable.argtypes = [C.c_int]
+    L.soar_kernel_timing_enable.restype = None
+    L.soar_kernel_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
+    L.soar_kernel_timing_read.restype = i32
+    L.soar_status_string.argtypes = [i32]
+    L.soar_status_string.restype = C.c_char_p
+    L.soar_version.argtypes = []
+    L.soar_version.restype = C.c_uint32
+    _lib = L
+    return L
+
+
+# ------------------------------------------------------------------ raw entry points
+def soar_default_params(method: int = SOAR_METHOD_SOAR, dss_radius: int = 4,
+                        search_mode: int = SOAR_SEARCH_AUTO, tiles_per_wg: int = 0) -> soar_params:
+    p = soar_params()
+    lib().soar_default_params(C.byref(p))
+    p.method = method
+    p.dss_radius = dss_radius
+    p.search_mode = search_mode
+    p.tiles_per_wg = tiles_per_wg
+    return p
+
+
+def soar_workspace_bytes(rows: int, cols: int, params: soar_params) -> int:
+    return int(lib().soar_workspace_bytes(rows, cols, C.byref(params)))
+
+
+def soar_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
+                  d_sse, d_status, d_workspace, workspace_bytes, hip_stream) -> int:
+    """Raw call: device addresses as integers; returns the soar_status code."""
+    return int(lib().soar_quantize(d_w, dtype, rows, cols, ld_elems, C.byref(params), d_codes, d_scales,
+                                   d_global_scale, d_sse, d_status, d_workspace, workspace_bytes,
+                                   hip_stream))
+
+
+def soar_quantize_batch(descs: Sequence[soar_tensor_desc], params, d_workspace, workspace_bytes,
+                        hip_stream) -> int:
+    arr = (soar_tensor_desc * len(descs))(*descs)
+    return int(lib().soar_quantize_batch(len(descs), arr, C.byref(params), d_workspace, workspace_bytes,
+                                         hip_stream))
+
+
+def soar_dequantize(d_codes, d_scales, d_global_scale, rows, cols, out_dtype, d_out, ld_elems,
+                    hip_stream) -> int:
+    return int(lib().soar_dequantize(d_codes, d_scales, d_global_scale, rows, cols, out_dtype, d_out,
+                                     ld_elems, hip_stream))
+
+
+def soar_recon_error(d_w, dtype, rows, cols, ld_elems, d_codes, d_scales, d_global_scale, d_sse,
+                     hip_stream) -> int:
+    return int(lib().soar_recon_error(d_w, dtype, rows, cols, ld_elems, d_codes, d_scales,
+                                      d_global_scale, d_sse, hip_stream))
+
+
+def soar_e2m1_round_f32(d_x, n, d_out, hip_stream) -> int:
+    return int(lib().soar_e2m1_round_f32(d_x, n, d_out, hip_stream))
+
+
+def soar_e4m3_project_f32(d_x, n, d_out, hip_stream) -> int:
+    return int(lib().soar_e4m3_project_f32(d_x, n, d_out, hip_stream))
+
+
+def soar_kernel_timing_enable(enable: bool) -> None:
+    lib().soar_kernel_timing_enable(1 if enable else 0)
+
+
+def soar_kernel_timing_read(kernel_id: int):
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    rc = lib().soar_kernel_timing_read(kernel_id, C.byref(ms), C.byref(n))
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_kernel_timing_read")
+    return ms.value, n.value
+
+
+def soar_version() -> int:
+    return int(lib().soar_version())
+
+
+# ------------------------------------------------------------------ tensor-level helpers
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return SOAR_BF16
+    if t.dtype == torch.float32:
+        return SOAR_FP32
+    raise TypeError("weights must be bfloat16 or float32")
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _check_matrix(w: torch.Tensor):
+    if not w.is_cuda:
+        raise RuntimeError("soar: weights must live on the GPU (no CPU path exists)")
+    if w.dim() != 2 or w.stride(1) != 1:
+        raise ValueError("weights must be 2-D with contiguous rows")
+    return w.shape[0], w.shape[1], w.stride(0)
+
+
+@dataclass
+class Quantized:
+    codes: torch.Tensor          # uint8 [rows, cols/2]
+    scales: torch.Tensor         # uint8 [rows, cols/16]
+    global_scale: torch.Tensor   # float32 [1]
+    sse: torch.Tensor            # float64 [1]
+    status: torch.Tensor         # int32 [1]
+
+
+def new_workspace(rows: int, cols: int, params: soar_params, device) -> torch.Tensor:
+    n = soar_workspace_bytes(rows, cols, params)
+    if n == 0:
+        raise SoarError(2, "soar_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def quantize(w: torch.Tensor, method: int = SOAR_METHOD_SOAR, dss_radius: int = 4,
+             search_mode: int = SOAR_SEARCH_AUTO, workspace: Optional[torch.Tensor] = None,
+             out: Optional[Quantized] = None, tiles_per_wg: int = 0) -> Quantized:
+    rows, cols, ld = _check_matrix(w)
+    p = soar_default_params(method, dss_radius, search_mode, tiles_per_wg)
+    dev = w.device
+    if out is None:
+        out = Quantized(torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev),
+                        torch.empty((rows, cols // 16), dtype=torch.uint8, device=dev),
+                        torch.empty(1, dtype=torch.float32, device=dev),
+                        torch.empty(1, dtype=torch.float64, device=dev),
+                        torch.empty(1, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = new_workspace(rows, cols, p, dev)
+    rc = soar_quantize(w.data_ptr(), _dtype_code(w), rows, cols, ld, p, out.codes.data_ptr(),
+                       out.scales.data_ptr(), out.global_scale.data_ptr(), out.sse.data_ptr(),
+                       out.status.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_quantize")
+    return out
+
+
+def make_desc(w: torch.Tensor, out: Quantized) -> soar_tensor_desc:
+    rows, cols, ld = _check_matrix(w)
+    return soar_tensor_desc(w.data_ptr(), _dtype_code(w), rows, cols, ld, out.codes.data_ptr(),
+                            out.scales.data_ptr(), out.global_scale.data_ptr(), out.sse.data_ptr(),
+                            out.status.data_ptr())
+
+
+def quantize_batch(descs: Sequence[soar_tensor_desc], params: soar_params, workspace: torch.Tensor) -> None:
+    rc = soar_quantize_batch(descs, params, workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_quantize_batch")
+
+
+def dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:
+    rows, cols = q.scales.shape[0], q.scales.shape[1] * 16
+    out = torch.empty((rows, cols), dtype=out_dtype, device=q.codes.device)
+    rc = soar_dequantize(q.codes.data_ptr(), q.scales.data_ptr(), q.global_scale.data_ptr(), rows, cols,
+                         _dtype_code(out), out.data_ptr(), cols, _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_dequantize")
+    return out
+
+
+def recon_error(w: torch.Tensor, q: Quantized) -> torch.Tensor:
+    rows, cols, ld = _check_matrix(w)
+    sse = torch.empty(1, dtype=torch.float64, device=w.device)
+    rc = soar_recon_error(w.data_ptr(), _dtype_code(w), rows, cols, ld, q.codes.data_ptr(),
+                          q.scales.data_ptr(), q.global_scale.data_ptr(), sse.data_ptr(), _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_recon_error")
+    return sse

@@ -1,0 +1,817 @@
+// SOAR NVFP4 weight quantization for MI355X (gfx950): HIP kernels and C-ABI.
+//
+// Path (arXiv 2605.12245, Algorithm 1 with T = 1 and beta = 1):
+//   absmax kernel   max|W|                      -> alpha0            (Eq. 1)
+//   stats kernel    per block: Delta0, Q0, a=sum wq, b=sum q^2       (Eq. 1-2)
+//                   tensor:    N=sum a*Delta0, M=sum b*Delta0^2      (Eq. 5)
+//                   last workgroup: alpha1 = N/M
+//   search kernel   per block: Delta* = a/(alpha1 b) (Eq. 6), centre = E4M3(Delta*)
+//                   (Appendix D), Q1 = Q_FP4(W/(alpha1 Delta*)), search of the
+//                   stored scale over centre-K..centre+K by Eq. 8, pack, error sum
+//
+// Work decomposition: one lane owns one 16-element block (two 128-bit loads for
+// bf16), so every per-block reduction is a register chain and no cross-lane
+// traffic is needed on the per-element path.  A workgroup of 256 lanes owns a
+// "tile" of 256 consecutive blocks.  The two tensor-wide sums are binary64
+// adjacent-pair trees over the flat block index; a wave butterfly, a 4-wave LDS
+// step and a binary-counter stack per workgroup reproduce that tree exactly for
+// any power-of-two number of tiles per workgroup.
+//
+// Build: hipcc --offload-arch=gfx950 -O3 -ffp-contract=off (no fast-math): every
+// float operation below is a separate IEEE binary32 operation unless written as
+// __builtin_fmaf, divisions are correctly rounded, subnormals are kept.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "soar.h"
+
+namespace {
+
+constexpr int kWG = 256;                 // lanes per workgroup = blocks per tile
+constexpr int kMaxPartials = 4096;       // workgroups per reduction kernel, at most
+constexpr size_t kCtrlBytes = 256;
+constexpr uint32_t kE4M3Min = 0x01u, kE4M3Max = 0x7Eu;
+
+struct Ctrl {
+    uint32_t amax_bits;      // max |w| as binary32 bits (atomicMax)
+    uint32_t ticket_stats;   // workgroups of the stats kernel that have finished
+    uint32_t ticket_search;  // same for the search kernel
+    uint32_t pad;
+    float    alpha0;
+    float    alpha1;
+    double   N, M;
+};
+static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
+
+struct Geom {
+    const void *w;
+    int64_t  ld;             // leading dimension, elements
+    uint32_t bpr;            // blocks per row
+    uint32_t nblk;           // blocks in the tensor
+    uint32_t tiles_per_wg;   // power of two
+    uint32_t contiguous;     // ld == cols
+};
+
+// ------------------------------------------------------------------ formats
+__device__ __forceinline__ float f_of(uint32_t u) { return __uint_as_float(u); }
+
+// positive E4M3 code -> value.  code<<20 read as binary32 has the same exponent
+// and mantissa fields with a bias off by 120, subnormals included.
+__device__ __forceinline__ float e4m3_value(uint32_t code) { return f_of(code << 20) * 0x1p120f; }
+
+// Appendix D: round to nearest even onto E4M3, clip to [2^-9, 448]
+__device__ __forceinline__ uint32_t e4m3_project(float y)
+{
+    y = fminf(fmaxf(y, 0.0f), 448.0f);            // NaN -> 0
+    uint32_t u = __float_as_uint(y);
+    u += 0x7FFFFu + ((u >> 20) & 1u);             // RNE to 3 mantissa bits
+    uint32_t normal = (u >> 20) - (120u << 3);
+    uint32_t sub = (uint32_t)__float2int_rn(y * 512.0f);
+    uint32_t code = (y >= 0x1p-6f) ? normal : sub;
+    return min(max(code, kE4M3Min), kE4M3Max);
+}
+
+// Eq. 2 on eight values: hardware E2M1 conversion (round to nearest even,
+// saturating, sign kept on zero), element 0 in the lowest nibble.
+__device__ __forceinline__ uint32_t fp4x8(const float *x)
+{
+    uint32_t r = 0;
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[0], x[1], 1.0f, 0);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[2], x[3], 1.0f, 1);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[4], x[5], 1.0f, 2);
+    r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, x[6], x[7], 1.0f, 3);
+    return r;
+}
+
+__device__ __forceinline__ void fp4x8_values(uint32_t r, float *q)
+{
+    auto v0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r, 1.0f, 0);
+    auto v1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r, 1.0f, 1);
+    auto v2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r, 1.0f, 2);
+    auto v3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r, 1.0f, 3);
+    q[0] = v0[0]; q[1] = v0[1]; q[2] = v1[0]; q[3] = v1[1];
+    q[4] = v2[0]; q[5] = v2[1]; q[6] = v3[0]; q[7] = v3[1];
+}
+
+// ------------------------------------------------------------------ loads
+template <int DT>
+__device__ __forceinline__ void load_block(const void *base, size_t elem_off, float w[16])
+{
+    if constexpr (DT == SOAR_BF16) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + elem_off);
+        uint4 v0 = p[0], v1 = p[1];
+        uint32_t u[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            w[2 * k] = f_of(u[k] << 16);
+            w[2 * k + 1] = f_of(u[k] & 0xFFFF0000u);
+        }
+    } else {
+        const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem_off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float4 v = p[k];
+            w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+        }
+    }
+}
+
+__device__ __forceinline__ size_t block_offset(const Geom &g, uint32_t i)
+{
+    if (g.contiguous) return (size_t)i * 16;
+    uint32_t row = i / g.bpr;
+    uint32_t cb = i - row * g.bpr;
+    return (size_t)row * (size_t)g.ld + (size_t)cb * 16;
+}
+
+// ------------------------------------------------------------------ per-block steps
+// Q = Q_FP4(W / scale) as a product with the correctly rounded reciprocal
+__device__ __forceinline__ void assign_codes(const float w[16], float scale, uint32_t nib[2], float q[16])
+{
+    float r = 1.0f / scale;
+    float x[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = w[j] * r;
+    nib[0] = fp4x8(x);
+    nib[1] = fp4x8(x + 8);
+    fp4x8_values(nib[0], q);
+    fp4x8_values(nib[1], q + 8);
+}
+
+// Eq. 8 for one candidate scale s = alpha * d: ascending chain of fused operations
+__device__ __forceinline__ float block_error(const float w[16], const float q[16], float s)
+{
+    float err = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        float e = __builtin_fmaf(-q[j], s, w[j]);
+        err = __builtin_fmaf(e, e, err);
+    }
+    return err;
+}
+
+__device__ __forceinline__ void block_sums(const float w[16], const float q[16], float &a, float &b)
+{
+    a = 0.0f; b = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        a = __builtin_fmaf(w[j], q[j], a);
+        b = __builtin_fmaf(q[j], q[j], b);
+    }
+}
+
+// Eq. 1 block scale and Eq. 2 assignment under (alpha0, Delta0)
+__device__ __forceinline__ void block_init(const float w[16], float alpha0, float alpha0_m,
+                                           uint32_t &c0, float &delta0, uint32_t nib[2], float q[16])
+{
+    float bmax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) bmax = fmaxf(bmax, fabsf(w[j]));
+    c0 = e4m3_project(bmax / alpha0_m);
+    delta0 = e4m3_value(c0);
+    assign_codes(w, alpha0 * delta0, nib, q);
+}
+
+// ------------------------------------------------------------------ reductions
+__device__ __forceinline__ double wave_pair_tree(double v)
+{
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) v = v + __shfl_xor(v, s, 64);
+    return v;
+}
+
+// tree over the per-workgroup partial sums part[0..P), zero-padded to a power
+// of two; all 256 lanes must call; result valid in every lane
+__device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */)
+{
+    uint32_t P2 = 1;
+    while (P2 < P) P2 <<= 1;
+    const uint32_t C = P2 > (uint32_t)kWG ? P2 / kWG : 1;     // <= 16
+    const uint32_t tid = threadIdx.x;
+    double v[16];
+#pragma unroll
+    for (uint32_t k = 0; k < 16; ++k) {
+        uint32_t idx = tid * C + k;
+        v[k] = (k < C && idx < P)
+                   ? __hip_atomic_load(part + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                   : 0.0;
+    }
+#pragma unroll
+    for (int s = 1; s < 16; s <<= 1)
+#pragma unroll
+        for (int k = 0; k < 16; k += 2 * s) v[k] = v[k] + v[k + s];
+    __syncthreads();
+    lds[tid] = v[0];
+    __syncthreads();
+    for (uint32_t n = kWG; n > 1; n >>= 1) {
+        double t = 0.0;
+        if (tid < n / 2) t = lds[2 * tid] + lds[2 * tid + 1];
+        __syncthreads();
+        if (tid < n / 2) lds[tid] = t;
+        __syncthreads();
+    }
+    return lds[0];
+}
+
+// ------------------------------------------------------------------ kernels
+__global__ void k_init(Ctrl *ctrl)
+{
+    uint32_t *p = reinterpret_cast<uint32_t *>(ctrl);
+    if (threadIdx.x < sizeof(Ctrl) / 4) p[threadIdx.x] = 0u;
+}
+
+// max |w| over a tensor.  |bits| of finite floats order like the values; NaN
+// and Inf patterns are larger than every finite one, so they surface in the max.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_absmax(const void *w, int64_t rows, int64_t row_chunks,
+                                                int64_t ld_chunks, Ctrl *ctrl)
+{
+    // a "chunk" is 16 bytes; a row holds row_chunks of them, rows are ld_chunks apart
+    const uint4 *base = static_cast<const uint4 *>(w);
+    uint32_t m = 0;
+    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
+        const uint4 *p = base + r * ld_chunks;
+        for (int64_t c = (int64_t)blockIdx.x * kWG + threadIdx.x; c < row_chunks; c += (int64_t)gridDim.x * kWG) {
+            uint4 v = p[c];
+            if constexpr (DT == SOAR_BF16) {
+                uint32_t a0 = v.x & 0x7FFF7FFFu, a1 = v.y & 0x7FFF7FFFu, a2 = v.z & 0x7FFF7FFFu, a3 = v.w & 0x7FFF7FFFu;
+                m = max(m, max(max(a0 & 0xFFFFu, a0 >> 16), max(a1 & 0xFFFFu, a1 >> 16)));
+                m = max(m, max(max(a2 & 0xFFFFu, a2 >> 16), max(a3 & 0xFFFFu, a3 >> 16)));
+            } else {
+                m = max(m, max(max(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu), max(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
+            }
+        }
+    }
+    if constexpr (DT == SOAR_BF16) m <<= 16;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&ctrl->amax_bits, m);
+}
+
+// Eq. 1-2 per block and the two tensor-wide sums of Eq. 5
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_stats(Geom g, Ctrl *ctrl, double *partN, double *partM,
+                                               float *d_global_scale)
+{
+    __shared__ double s_wave[2][4];
+    __shared__ double s_stack[2][32];
+    __shared__ double s_tree[kWG];
+    __shared__ uint32_t s_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t amax_bits = ctrl->amax_bits;
+    const bool degenerate = amax_bits == 0u || amax_bits >= 0x7F800000u;
+    const float alpha0 = f_of(amax_bits) / 2688.0f;
+    const float alpha0_m = alpha0 * 6.0f;
+
+    double wgN = 0.0, wgM = 0.0;
+    const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
+    for (uint32_t k = 0; k < g.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        double tN = 0.0, tM = 0.0;
+        if (i < g.nblk && !degenerate) {
+            float w[16], q[16];
+            uint32_t nib[2], c0;
+            float delta0, a, b;
+            load_block<DT>(g.w, block_offset(g, i), w);
+            block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+            block_sums(w, q, a, b);
+            tN = (double)a * (double)delta0;
+            tM = ((double)b * (double)delta0) * (double)delta0;
+        }
+        tN = wave_pair_tree(tN);
+        tM = wave_pair_tree(tM);
+        if ((tid & 63) == 0) { s_wave[0][tid >> 6] = tN; s_wave[1][tid >> 6] = tM; }
+        __syncthreads();
+        if (tid == 0) {
+            // tile sum, then binary-counter stack: tile k closes every level whose bit of k is set
+            double vN = (s_wave[0][0] + s_wave[0][1]) + (s_wave[0][2] + s_wave[0][3]);
+            double vM = (s_wave[1][0] + s_wave[1][1]) + (s_wave[1][2] + s_wave[1][3]);
+            uint32_t lvl = 0;
+            while ((k >> lvl) & 1u) {
+                vN = s_stack[0][lvl] + vN;
+                vM = s_stack[1][lvl] + vM;
+                ++lvl;
+            }
+            s_stack[0][lvl] = vN;
+            s_stack[1][lvl] = vM;
+            wgN = vN; wgM = vM;          // after the last tile: the sum of all tiles
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        partN[blockIdx.x] = wgN;
+        partM[blockIdx.x] = wgM;
+        __threadfence();
+        uint32_t t = __hip_atomic_fetch_add(&ctrl->ticket_stats, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // last workgroup to arrive: finish the trees and apply Eq. 5
+    __threadfence();
+    double N = tree_of_partials(partN, gridDim.x, s_tree);
+    double M = tree_of_partials(partM, gridDim.x, s_tree);
+    if (tid == 0) {
+        float alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;
+        if (amax_bits == 0u) alpha1 = 1.0f;
+        ctrl->alpha0 = alpha0;
+        ctrl->alpha1 = alpha1;
+        ctrl->N = N;
+        ctrl->M = M;
+        *d_global_scale = alpha1;
+    }
+}
+
+// Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
+// METHOD RTN emits the Eq. 1-2 state instead.
+template <int DT, int METHOD>
+__global__ __launch_bounds__(kWG) void k_search(Geom g, Ctrl *ctrl, int radius, uint8_t *codes, uint8_t *scales,
+                                                double *partS, float *d_global_scale, double *d_sse,
+                                                int32_t *d_status)
+{
+    __shared__ double s_wave[4];
+    __shared__ double s_tree[kWG];
+    __shared__ uint32_t s_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t amax_bits = ctrl->amax_bits;
+    const bool allzero = amax_bits == 0u;
+    const float alpha0 = f_of(amax_bits) / 2688.0f;
+    const float alpha0_m = alpha0 * 6.0f;
+    const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? ctrl->alpha1 : alpha0;
+
+    double sse = 0.0;
+    const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
+    for (uint32_t k = 0; k < g.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        if (i >= g.nblk) continue;
+        float w[16], q[16];
+        uint32_t nib[2], c0;
+        float delta0;
+        load_block<DT>(g.w, block_offset(g, i), w);
+        uint32_t out_code;
+        float out_err;
+        if (allzero) {
+            // every weight is +-0: smallest scale, zero codes carrying the sign
+            float x[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) x[j] = w[j];
+            nib[0] = fp4x8(x);
+            nib[1] = fp4x8(x + 8);
+            out_code = kE4M3Min;
+            out_err = 0.0f;
+        } else {
+            block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+            if constexpr (METHOD == SOAR_METHOD_RTN) {
+                out_code = c0;
+                out_err = block_error(w, q, alpha0 * delta0);
+            } else {
+                float a, b;
+                block_sums(w, q, a, b);
+                const float delta_star = (b == 0.0f) ? delta0 : a / (alpha1 * b);
+                const int centre = (int)e4m3_project(delta_star);
+                assign_codes(w, alpha1 * delta_star, nib, q);
+                int best = centre;
+                float best_err = block_error(w, q, alpha1 * e4m3_value((uint32_t)centre));
+                for (int o = 1; o <= radius; ++o) {
+                    // a code outside [0x01, 0x7E] is clamped onto an already evaluated
+                    // candidate and can then never be strictly better
+                    int cm = max(centre - o, (int)kE4M3Min);
+                    float em = block_error(w, q, alpha1 * e4m3_value((uint32_t)cm));
+                    if (em < best_err) { best_err = em; best = cm; }
+                    int cp = min(centre + o, (int)kE4M3Max);
+                    float ep = block_error(w, q, alpha1 * e4m3_value((uint32_t)cp));
+                    if (ep < best_err) { best_err = ep; best = cp; }
+                }
+                out_code = (uint32_t)best;
+                out_err = best_err;
+            }
+        }
+        reinterpret_cast<uint2 *>(codes)[i] = make_uint2(nib[0], nib[1]);
+        scales[i] = (uint8_t)out_code;
+        sse += (double)out_err;
+    }
+    // error sum: fixed order for a given launch shape
+    sse = wave_pair_tree(sse);
+    if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
+    __syncthreads();
+    if (tid == 0) {
+        partS[blockIdx.x] = (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]);
+        __threadfence();
+        uint32_t t = __hip_atomic_fetch_add(&ctrl->ticket_search, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    double total = tree_of_partials(partS, gridDim.x, s_tree);
+    if (tid == 0) {
+        if (d_sse) *d_sse = total;
+        if (d_status)
+            *d_status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
+        if (METHOD == SOAR_METHOD_RTN) *d_global_scale = allzero ? 1.0f : alpha0;
+    }
+}
+
+// Eq. 3
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
+                                                 const float *d_global_scale, Geom g, void *out)
+{
+    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    if (i >= g.nblk) return;
+    const float s = *d_global_scale * e4m3_value(scales[i]);
+    const uint2 nb = reinterpret_cast<const uint2 *>(codes)[i];
+    float q[16];
+    fp4x8_values(nb.x, q);
+    fp4x8_values(nb.y, q + 8);
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = q[j] * s;
+    const size_t off = block_offset(g, i);
+    if constexpr (DT == SOAR_BF16) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        uint32_t u[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            f2 in = {v[2 * k], v[2 * k + 1]};
+            bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
+            __builtin_memcpy(&u[k], &o, 4);
+        }
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + off);
+        p[0] = make_uint4(u[0], u[1], u[2], u[3]);
+        p[1] = make_uint4(u[4], u[5], u[6], u[7]);
+    } else {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    }
+}
+
+__global__ void k_zero_f64(double *p) { *p = 0.0; }
+
+// Eq. 4 for stored codes and scales
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_recon(Geom g, const uint8_t *codes, const uint8_t *scales,
+                                               const float *d_global_scale, double *d_sse)
+{
+    __shared__ double s_wave[4];
+    const uint32_t tid = threadIdx.x;
+    const float alpha = *d_global_scale;
+    double sse = 0.0;
+    for (uint32_t i = blockIdx.x * kWG + tid; i < g.nblk; i += gridDim.x * kWG) {
+        float w[16], q[16];
+        load_block<DT>(g.w, block_offset(g, i), w);
+        const uint2 nb = reinterpret_cast<const uint2 *>(codes)[i];
+        fp4x8_values(nb.x, q);
+        fp4x8_values(nb.y, q + 8);
+        sse += (double)block_error(w, q, alpha * e4m3_value(scales[i]));
+    }
+    sse = wave_pair_tree(sse);
+    if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
+    __syncthreads();
+    if (tid == 0) atomicAdd(d_sse, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
+}
+
+__global__ void k_e2m1_round(const float *x, int64_t n, uint8_t *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (uint8_t)(__builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[i], 0.0f, 1.0f, 0) & 0xFu);
+}
+
+__global__ void k_e4m3_project(const float *x, int64_t n, uint8_t *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (uint8_t)e4m3_project(x[i]);
+}
+
+// ------------------------------------------------------------------ host side
+struct Timing {
+    bool enabled = false;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[SOAR_KERNEL_COUNT];
+    std::vector<hipEvent_t> pool;
+};
+Timing g_timing;
+
+struct ScopedTimer {
+    int id;
+    hipStream_t st;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ScopedTimer(int id_, hipStream_t st_) : id(id_), st(st_)
+    {
+        if (!g_timing.enabled) return;
+        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e0 = e1 = nullptr; return; }
+        (void)hipEventRecord(e0, st);
+    }
+    ~ScopedTimer()
+    {
+        if (!e0) return;
+        (void)hipEventRecord(e1, st);
+        g_timing.ev[id].emplace_back(e0, e1);
+    }
+};
+
+bool valid_params(const soar_params *p)
+{
+    if (!p || p->struct_size != sizeof(soar_params)) return false;
+    if (p->method != SOAR_METHOD_RTN && p->method != SOAR_METHOD_SOAR) return false;
+    if (p->block != 16 || p->iters != 1 || p->n_beta != 1) return false;
+    if (p->beta_lo != 1.0f || p->beta_hi != 1.0f) return false;
+    if (p->dss_radius < 0 || p->dss_radius > 125) return false;
+    if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
+    if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    return true;
+}
+
+soar_status check_shape(int64_t rows, int64_t cols, int64_t ld)
+{
+    if (rows <= 0 || cols <= 0 || cols % 16 != 0 || ld < cols) return SOAR_ERR_SHAPE;
+    // block count must fit the kernels' 32-bit block index with a tile of slack
+    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31) return SOAR_ERR_SHAPE;
+    if (rows * (cols / 16) > ((int64_t)1 << 31) - 2 * kWG) return SOAR_ERR_SHAPE;
+    return SOAR_OK;
+}
+
+soar_status check_matrix_ptr(const void *p, int dtype, int64_t ld)
+{
+    const int64_t es = dtype == SOAR_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return SOAR_ERR_ALIGN;
+    if ((ld * es) % 16 != 0) return SOAR_ERR_ALIGN;
+    return SOAR_OK;
+}
+
+Geom make_geom(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t *n_wg, uint32_t forced_tpw = 0)
+{
+    Geom g;
+    g.w = w;
+    g.ld = ld;
+    g.bpr = (uint32_t)(cols / 16);
+    g.nblk = (uint32_t)(rows * (cols / 16));
+    g.contiguous = (ld == cols) ? 1u : 0u;
+    const uint32_t tiles = (g.nblk + kWG - 1) / kWG;
+    uint32_t tpw = 1;
+    if (forced_tpw) tpw = forced_tpw;
+    while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
+    g.tiles_per_wg = tpw;
+    *n_wg = (tiles + tpw - 1) / tpw;
+    return g;
+}
+
+#define SOAR_LAUNCH_CHECK()                                  \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return SOAR_ERR_HIP; \
+    } while (0)
+
+soar_status validate_quantize(const void *d_w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                              const soar_params *params, const uint8_t *d_codes, const uint8_t *d_scales,
+                              const float *d_global_scale, const void *d_workspace, size_t workspace_bytes)
+{
+    if (!d_w || !d_codes || !d_scales || !d_global_scale || !params) return SOAR_ERR_NULL;
+    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    if (!valid_params(params)) return SOAR_ERR_PARAM;
+    soar_status s = check_shape(rows, cols, ld);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(d_w, dtype, ld);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
+    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
+    if (workspace_bytes < soar_workspace_bytes(rows, cols, params)) return SOAR_ERR_WORKSPACE;
+    return SOAR_OK;
+}
+
+template <int DT>
+soar_status enqueue_quantize(const void *d_w, int64_t rows, int64_t cols, int64_t ld, const soar_params *params,
+                             uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale, double *d_sse,
+                             int32_t *d_status, void *d_workspace, hipStream_t st)
+{
+    Ctrl *ctrl = static_cast<Ctrl *>(d_workspace);
+    double *partN = reinterpret_cast<double *>(static_cast<char *>(d_workspace) + kCtrlBytes);
+    double *partM = partN + kMaxPartials;
+    double *partS = partM + kMaxPartials;
+    uint32_t n_wg = 0;
+    const Geom g = make_geom(d_w, rows, cols, ld, &n_wg, (uint32_t)params->tiles_per_wg);
+    const int64_t es = DT == SOAR_BF16 ? 2 : 4;
+
+    {
+        ScopedTimer t(SOAR_KERNEL_INIT, st);
+        hipLaunchKernelGGL(k_init, dim3(1), dim3(64), 0, st, ctrl);
+        SOAR_LAUNCH_CHECK();
+    }
+    {
+        ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
+        int64_t a_rows = rows, row_chunks = cols * es / 16, ld_chunks = ld * es / 16;
+        if (ld == cols) { row_chunks *= rows; a_rows = 1; ld_chunks = row_chunks; }
+        int64_t gx = (row_chunks + (int64_t)kWG * 4 - 1) / ((int64_t)kWG * 4);
+        if (gx > 2048) gx = 2048;
+        if (gx < 1) gx = 1;
+        int64_t gy = a_rows;
+        const int64_t gy_cap = (4096 + gx - 1) / gx;
+        if (gy > gy_cap) gy = gy_cap;
+        hipLaunchKernelGGL(k_absmax<DT>, dim3((uint32_t)gx, (uint32_t)gy), dim3(kWG), 0, st, d_w, a_rows,
+                           row_chunks, ld_chunks, ctrl);
+        SOAR_LAUNCH_CHECK();
+    }
+    if (params->method == SOAR_METHOD_SOAR) {
+        {
+            ScopedTimer t(SOAR_KERNEL_STATS, st);
+            hipLaunchKernelGGL(k_stats<DT>, dim3(n_wg), dim3(kWG), 0, st, g, ctrl, partN, partM, d_global_scale);
+            SOAR_LAUNCH_CHECK();
+        }
+        ScopedTimer t(SOAR_KERNEL_SEARCH, st);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(n_wg), dim3(kWG), 0, st, g, ctrl,
+                           params->dss_radius, d_codes, d_scales, partS, d_global_scale, d_sse, d_status);
+        SOAR_LAUNCH_CHECK();
+    } else {
+        ScopedTimer t(SOAR_KERNEL_SEARCH, st);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ctrl, 0, d_codes,
+                           d_scales, partS, d_global_scale, d_sse, d_status);
+        SOAR_LAUNCH_CHECK();
+    }
+    return SOAR_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C-ABI
+extern "C" {
+
+void soar_default_params(soar_params *p)
+{
+    if (!p) return;
+    std::memset(p, 0, sizeof(*p));
+    p->struct_size = sizeof(soar_params);
+    p->method = SOAR_METHOD_SOAR;
+    p->block = 16;
+    p->iters = 1;
+    p->dss_radius = 4;
+    p->n_beta = 1;
+    p->beta_lo = 1.0f;
+    p->beta_hi = 1.0f;
+    p->early_stop_rel = 1e-3f;
+    p->search_mode = SOAR_SEARCH_AUTO;
+}
+
+size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)
+{
+    if (!valid_params(params) || check_shape(rows, cols, cols) != SOAR_OK) return 0;
+    return kCtrlBytes + 3 * sizeof(double) * (size_t)kMaxPartials;
+}
+
+soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
+                          const soar_params *params, uint8_t *d_codes, uint8_t *d_scales,
+                          float *d_global_scale, double *d_sse, int32_t *d_status, void *d_workspace,
+                          size_t workspace_bytes, void *hip_stream)
+{
+    soar_status s = validate_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales,
+                                      d_global_scale, d_workspace, workspace_bytes);
+    if (s != SOAR_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (dtype == SOAR_BF16)
+        return enqueue_quantize<SOAR_BF16>(d_w, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
+                                           d_sse, d_status, d_workspace, st);
+    return enqueue_quantize<SOAR_FP32>(d_w, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
+                                       d_sse, d_status, d_workspace, st);
+}
+
+soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params,
+                                void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (n < 0) return SOAR_ERR_SHAPE;
+    if (n > 0 && !descs) return SOAR_ERR_NULL;
+    for (int32_t k = 0; k < n; ++k) {
+        const soar_tensor_desc &d = descs[k];
+        soar_status s = validate_quantize(d.d_w, d.dtype, d.rows, d.cols, d.ld_elems, params, d.d_codes,
+                                          d.d_scales, d.d_global_scale, d_workspace, workspace_bytes);
+        if (s != SOAR_OK) return s;
+    }
+    for (int32_t k = 0; k < n; ++k) {
+        const soar_tensor_desc &d = descs[k];
+        soar_status s = soar_quantize(d.d_w, (soar_dtype)d.dtype, d.rows, d.cols, d.ld_elems, params, d.d_codes,
+                                      d.d_scales, d.d_global_scale, d.d_sse, d.d_status, d_workspace,
+                                      workspace_bytes, hip_stream);
+        if (s != SOAR_OK) return s;
+    }
+    return SOAR_OK;
+}
+
+soar_status soar_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, const float *d_global_scale,
+                            int64_t rows, int64_t cols, soar_dtype out_dtype, void *d_out, int64_t ld_elems,
+                            void *hip_stream)
+{
+    if (!d_codes || !d_scales || !d_global_scale || !d_out) return SOAR_ERR_NULL;
+    if (out_dtype != SOAR_BF16 && out_dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    soar_status s = check_shape(rows, cols, ld_elems);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(d_out, out_dtype, ld_elems);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    uint32_t n_wg = 0;
+    Geom g = make_geom(d_out, rows, cols, ld_elems, &n_wg);
+    const uint32_t grid = (g.nblk + kWG - 1) / kWG;
+    ScopedTimer t(SOAR_KERNEL_DEQUANT, st);
+    if (out_dtype == SOAR_BF16)
+        hipLaunchKernelGGL(k_dequant<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, d_global_scale, g, d_out);
+    else
+        hipLaunchKernelGGL(k_dequant<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, d_global_scale, g, d_out);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
+                             const uint8_t *d_codes, const uint8_t *d_scales, const float *d_global_scale,
+                             double *d_sse, void *hip_stream)
+{
+    if (!d_w || !d_codes || !d_scales || !d_global_scale || !d_sse) return SOAR_ERR_NULL;
+    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    soar_status s = check_shape(rows, cols, ld_elems);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(d_w, dtype, ld_elems);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    uint32_t n_wg = 0;
+    Geom g = make_geom(d_w, rows, cols, ld_elems, &n_wg);
+    uint32_t grid = (g.nblk + kWG - 1) / kWG;
+    if (grid > 2048) grid = 2048;
+    ScopedTimer t(SOAR_KERNEL_RECON, st);
+    hipLaunchKernelGGL(k_zero_f64, dim3(1), dim3(1), 0, st, d_sse);
+    SOAR_LAUNCH_CHECK();
+    if (dtype == SOAR_BF16)
+        hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
+    else
+        hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+soar_status soar_e2m1_round_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream)
+{
+    if (!d_x || !d_out) return SOAR_ERR_NULL;
+    if (n < 0 || n > ((int64_t)1 << 38)) return SOAR_ERR_SHAPE;
+    if (n == 0) return SOAR_OK;
+    hipLaunchKernelGGL(k_e2m1_round, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), d_x, n, d_out);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream)
+{
+    if (!d_x || !d_out) return SOAR_ERR_NULL;
+    if (n < 0 || n > ((int64_t)1 << 38)) return SOAR_ERR_SHAPE;
+    if (n == 0) return SOAR_OK;
+    hipLaunchKernelGGL(k_e4m3_project, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), d_x, n, d_out);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+void soar_kernel_timing_enable(int enable)
+{
+    for (auto &v : g_timing.ev) {
+        for (auto &p : v) { (void)hipEventDestroy(p.first); (void)hipEventDestroy(p.second); }
+        v.clear();
+    }
+    g_timing.enabled = enable != 0;
+}
+
+soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) return SOAR_ERR_NULL;
+    if (kernel_id < 0 || kernel_id >= SOAR_KERNEL_COUNT) return SOAR_ERR_PARAM;
+    double sum = 0.0;
+    for (auto &p : g_timing.ev[kernel_id]) {
+        if (hipEventSynchronize(p.second) != hipSuccess) return SOAR_ERR_HIP;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, p.first, p.second) != hipSuccess) return SOAR_ERR_HIP;
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)g_timing.ev[kernel_id].size();
+    return SOAR_OK;
+}
+
+const char *soar_status_string(soar_status s)
+{
+    switch (s) {
+    case SOAR_OK: return "ok";
+    case SOAR_ERR_NULL: return "null pointer";
+    case SOAR_ERR_SHAPE: return "bad shape";
+    case SOAR_ERR_DTYPE: return "bad dtype";
+    case SOAR_ERR_PARAM: return "bad parameter";
+    case SOAR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SOAR_ERR_HIP: return "HIP runtime error";
+    case SOAR_ERR_ALIGN: return "misaligned pointer or leading dimension";
+    }
+    return "unknown status";
+}
+
+uint32_t soar_version(void) { return 0x00010000u; }
+
+}  // extern "C"

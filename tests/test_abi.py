@@ -1,0 +1,85 @@
+"""The C-ABI library loads without a GPU, exports every symbol that
+include/soar.h declares, and rejects bad arguments on the host before
+anything is enqueued (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_12245_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "soar.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(soar_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert set(B.EXPORTS) == set(names)
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None, n
+
+
+def test_version_and_status_strings():
+    assert B.soar_version() >= 0x00010000
+    L = B.lib()
+    seen = {L.soar_status_string(k).decode() for k in range(8)}
+    assert len(seen) == 8 and "ok" in seen
+    assert L.soar_status_string(99).decode() == "unknown status"
+
+
+def test_default_params_and_workspace_query():
+    p = B.soar_default_params()
+    assert (p.struct_size, p.method, p.block, p.iters, p.dss_radius, p.n_beta) == (C.sizeof(B.soar_params), 1, 16, 1, 4, 1)
+    assert p.beta_lo == 1.0 and p.beta_hi == 1.0
+    n = B.soar_workspace_bytes(4096, 4096, p)
+    assert n > 0 and n % 256 == 0
+    assert B.soar_workspace_bytes(4096, 4090, p) == 0
+    assert B.soar_workspace_bytes(0, 4096, p) == 0
+    p.iters = 15
+    assert B.soar_workspace_bytes(4096, 4096, p) == 0
+
+
+def _q(p, d_w=0x1000, dtype=0, rows=64, cols=64, ld=64, codes=0x2000, scales=0x3000, gs=0x4000,
+       ws=0x10000, ws_bytes=1 << 20):
+    # the addresses are never dereferenced: every call below must fail validation
+    return B.soar_quantize(d_w, dtype, rows, cols, ld, p, codes, scales, gs, 0, 0, ws, ws_bytes, 0)
+
+
+def test_host_side_argument_validation():
+    p = B.soar_default_params()
+    assert _q(p, d_w=0) == 1 and _q(p, codes=0) == 1 and _q(p, scales=0) == 1 and _q(p, gs=0) == 1
+    assert _q(p, cols=40, ld=40) == 2 and _q(p, rows=0) == 2 and _q(p, ld=48) != 0 and _q(p, ld=32) == 2
+    assert _q(p, rows=1 << 31, cols=1 << 20, ld=1 << 20) == 2
+    assert _q(p, dtype=5) == 3
+    assert _q(p, d_w=0x1008) == 7 and _q(p, ld=68) == 7 and _q(p, codes=0x2004) == 7
+    assert _q(p, ws=0) == 5 and _q(p, ws=0x10010) == 5 and _q(p, ws_bytes=1000) == 5
+    for field, bad in (("method", 7), ("block", 32), ("iters", 2), ("dss_radius", -1), ("dss_radius", 200),
+                       ("n_beta", 101), ("beta_lo", 0.5), ("search_mode", 9), ("tiles_per_wg", 3),
+                       ("struct_size", 4)):
+        q = B.soar_default_params()
+        setattr(q, field, bad)
+        assert _q(q) == 4, field
+    assert B.soar_dequantize(0, 0x10, 0x20, 4, 64, 0, 0x1000, 64, 0) == 1
+    assert B.soar_dequantize(0x8, 0x10, 0x20, 4, 60, 0, 0x1000, 64, 0) == 2
+    assert B.soar_recon_error(0x1000, 0, 4, 64, 64, 0x8, 0x10, 0x20, 0, 0) == 1
+    assert B.soar_recon_error(0x1000, 3, 4, 64, 64, 0x8, 0x10, 0x20, 0x30, 0) == 3
+    assert B.soar_e2m1_round_f32(0, 4, 0x10, 0) == 1 and B.soar_e4m3_project_f32(0x10, -1, 0x10, 0) == 2
+    d = B.soar_tensor_desc(0x1000, 0, 64, 60, 64, 0x2000, 0x3000, 0x4000, 0, 0)
+    assert B.soar_quantize_batch([d], p, 0x10000, 1 << 20, 0) == 2
+    assert B.soar_quantize_batch([], p, 0x10000, 1 << 20, 0) == 0
+
+
+def test_product_path_has_no_cpu_route():
+    torch = pytest.importorskip("torch")
+    w = torch.zeros(16, 16, dtype=torch.bfloat16)
+    with pytest.raises(RuntimeError):
+        B.quantize(w)
+    src = open(os.path.join(ROOT, "paper_2605_12245_amd", "binding.py")).read()
+    assert "import oracle" not in src and "from oracle" not in src

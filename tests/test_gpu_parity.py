@@ -1,0 +1,246 @@
+"""GPU-vs-oracle parity, through the C-ABI (needs an MI355X: run with -m gpu).
+
+Bar: packed E2M1 codes and E4M3 scale bytes bit-exact; the FP32 global scale
+and the reconstruction error within 1e-6 relative (the global scale is in fact
+expected to be bit-identical, because the tensor-wide sums follow one fixed
+binary64 tree on both sides).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_12245_amd import binding as B
+from paper_2605_12245_amd import synth
+
+pytestmark = pytest.mark.gpu
+REL = 1e-6
+DEV = "cuda:0"
+
+
+def np_weights(w: torch.Tensor) -> np.ndarray:
+    w = w.detach().cpu()
+    if w.dtype == torch.bfloat16:
+        flat = w.contiguous().view(torch.int16).numpy().view(np.uint16)
+    else:
+        flat = w.contiguous().numpy()
+    return flat
+
+
+def check_against_oracle(w: torch.Tensor, method, K, search_mode=B.SOAR_SEARCH_AUTO, tiles_per_wg=0,
+                         what=""):
+    out = B.quantize(w, method, K, search_mode, tiles_per_wg=tiles_per_wg)
+    torch.cuda.synchronize()
+    host = np_weights(w) if w.is_contiguous() else None
+    if host is None:
+        # strided view: give the oracle the same view of a host copy of the parent
+        raise AssertionError("pass contiguous tensors here; strided cases use check_strided")
+    ref = oracle.quantize(host, method, K)
+    codes = out.codes.cpu().numpy()
+    scales = out.scales.cpu().numpy()
+    nbad_c = int((codes != ref.codes).sum())
+    nbad_s = int((scales != ref.scales).sum())
+    assert int(out.status.item()) == ref.status, what
+    if ref.status & oracle.STATUS_NONFINITE:
+        return out, ref
+    assert nbad_s == 0, f"{what}: {nbad_s} scale bytes differ"
+    assert nbad_c == 0, f"{what}: {nbad_c} code bytes differ"
+    g = np.float32(out.global_scale.item())
+    assert g == ref.global_scale, f"{what}: global scale {g!r} vs {ref.global_scale!r}"
+    sse = float(out.sse.item())
+    assert math.isclose(sse, ref.sse, rel_tol=REL, abs_tol=0.0), f"{what}: sse {sse} vs {ref.sse}"
+    return out, ref
+
+
+# ----------------------------------------------------------------- formats
+def test_e2m1_conversion_all_float32_patterns():
+    """hardware E2M1 conversion vs the oracle's Eq. 2 on every non-NaN float32"""
+    chunk = 1 << 26
+    out = torch.empty(chunk, dtype=torch.uint8, device=DEV)
+    base = torch.arange(chunk, dtype=torch.int64, device=DEV)
+    for c in range(0, 1 << 32, chunk):
+        bits = (base + c).to(torch.int32) if c < (1 << 31) else (base + (c - (1 << 32))).to(torch.int32)
+        x = bits.view(torch.float32)
+        assert B.soar_e2m1_round_f32(x.data_ptr(), chunk, out.data_ptr(), 0) == 0
+        got = out.cpu().numpy()
+        xh = (np.arange(chunk, dtype=np.uint32) + np.uint32(c)).view(np.float32)
+        want = oracle.e2m1_nibble_many(xh)
+        ok = np.isnan(xh) | (got == want)
+        assert ok.all(), f"chunk {c:#x}: {np.count_nonzero(~ok)} mismatches, first at {xh[~ok][:4]}"
+
+
+def test_e4m3_projection_all_float32_patterns():
+    chunk = 1 << 26
+    out = torch.empty(chunk, dtype=torch.uint8, device=DEV)
+    base = torch.arange(chunk, dtype=torch.int64, device=DEV)
+    for c in range(0, 1 << 32, chunk):
+        bits = (base + c).to(torch.int32) if c < (1 << 31) else (base + (c - (1 << 32))).to(torch.int32)
+        x = bits.view(torch.float32)
+        assert B.soar_e4m3_project_f32(x.data_ptr(), chunk, out.data_ptr(), 0) == 0
+        got = out.cpu().numpy()
+        xh = (np.arange(chunk, dtype=np.uint32) + np.uint32(c)).view(np.float32)
+        want = oracle.e4m3_project_many(xh)
+        bad = got != want
+        assert not bad.any(), f"chunk {c:#x}: {np.count_nonzero(bad)} mismatches, first at {xh[bad][:4]}"
+
+
+# ----------------------------------------------------------------- the five workloads
+@pytest.mark.parametrize("workload", [1, 2, 3])
+@pytest.mark.parametrize("method", [B.SOAR_METHOD_SOAR, B.SOAR_METHOD_RTN], ids=["soar", "rtn"])
+def test_single_tensor_workloads_full_size(workload, method):
+    spec = synth.workload_specs(workload)[0]
+    w = synth.make_weight(spec, DEV)
+    out, ref = check_against_oracle(w, method, spec.dss_radius, what=f"workload {workload}")
+    # Eq. 3 and Eq. 4 entry points on the same outputs
+    back = B.dequantize(out, torch.bfloat16).cpu().view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(back, oracle.dequantize(ref.codes, ref.scales, ref.global_scale, oracle.BF16))
+    back32 = B.dequantize(out, torch.float32).cpu().numpy()
+    assert np.array_equal(back32, oracle.dequantize(ref.codes, ref.scales, ref.global_scale, oracle.FP32))
+    sse = float(B.recon_error(w, out).item())
+    assert math.isclose(sse, ref.sse, rel_tol=REL)
+    if method == B.SOAR_METHOD_SOAR:
+        rtn = oracle.quantize(np_weights(w), oracle.METHOD_RTN, 0)
+        assert ref.sse <= rtn.sse
+
+
+@pytest.mark.parametrize("workload,div", [(4, 8), (5, 16)])
+def test_multi_tensor_workloads_scaled_down_batch(workload, div):
+    specs = synth.workload_specs(workload, div)[:21]
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, specs[0].dss_radius)
+    ws = B.new_workspace(max(s.rows for s in specs), max(s.cols for s in specs), p, DEV)
+    ws_list, outs, descs = [], [], []
+    for s in specs:
+        w = synth.make_weight(s, DEV)
+        o = B.Quantized(torch.empty((s.rows, s.cols // 2), dtype=torch.uint8, device=DEV),
+                        torch.empty((s.rows, s.cols // 16), dtype=torch.uint8, device=DEV),
+                        torch.empty(1, dtype=torch.float32, device=DEV),
+                        torch.empty(1, dtype=torch.float64, device=DEV),
+                        torch.empty(1, dtype=torch.int32, device=DEV))
+        ws_list.append(w); outs.append(o); descs.append(B.make_desc(w, o))
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    for s, w, o in zip(specs, ws_list, outs):
+        ref = oracle.quantize(np_weights(w), oracle.METHOD_SOAR, s.dss_radius)
+        assert np.array_equal(o.codes.cpu().numpy(), ref.codes), s.name
+        assert np.array_equal(o.scales.cpu().numpy(), ref.scales), s.name
+        assert np.float32(o.global_scale.item()) == ref.global_scale, s.name
+        assert math.isclose(float(o.sse.item()), ref.sse, rel_tol=REL), s.name
+        assert int(o.status.item()) == 0
+
+
+# ----------------------------------------------------------------- shapes and modes
+RAGGED = [(1, 16), (1, 48), (3, 48), (5, 112), (257, 16), (2, 4096), (64, 16 * 17), (1000, 272),
+          (255, 256), (513, 1040)]
+
+
+@pytest.mark.parametrize("rows,cols", RAGGED)
+def test_ragged_and_tiny_shapes(rows, cols):
+    g = torch.Generator(device="cpu").manual_seed(rows * 7919 + cols)
+    w = (torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g) * 2) * 0.02)
+    w = w.to(torch.bfloat16).to(DEV)
+    for method in (B.SOAR_METHOD_SOAR, B.SOAR_METHOD_RTN):
+        for K in (0, 1, 4, 8):
+            check_against_oracle(w, method, K, what=f"{rows}x{cols} m{method} K{K}")
+
+
+def test_search_mode_and_launch_shape_do_not_change_a_byte():
+    spec = synth.workload_specs(3, 4)[0]
+    w = synth.make_weight(spec, DEV)
+    base = B.quantize(w, B.SOAR_METHOD_SOAR, 8)
+    torch.cuda.synchronize()
+    for mode in (B.SOAR_SEARCH_AUTO, B.SOAR_SEARCH_FULL):
+        for tpw in (0, 1, 2, 8, 64, 4096):
+            o = B.quantize(w, B.SOAR_METHOD_SOAR, 8, mode, tiles_per_wg=tpw)
+            torch.cuda.synchronize()
+            assert torch.equal(o.codes, base.codes) and torch.equal(o.scales, base.scales), (mode, tpw)
+            assert o.global_scale.item() == base.global_scale.item(), (mode, tpw)
+            assert math.isclose(o.sse.item(), base.sse.item(), rel_tol=1e-12), (mode, tpw)
+    # and twice the same call: bit-identical including the error sum
+    o2 = B.quantize(w, B.SOAR_METHOD_SOAR, 8)
+    torch.cuda.synchronize()
+    assert o2.sse.item() == base.sse.item()
+
+
+def test_fp32_input_and_leading_dimension():
+    g = torch.Generator(device="cpu").manual_seed(5)
+    f = (torch.distributions.StudentT(4.0).sample((300, 528)) * 0.02).float()
+    check_against_oracle(f.to(DEV), B.SOAR_METHOD_SOAR, 4, what="fp32")
+    check_against_oracle(f.to(DEV), B.SOAR_METHOD_RTN, 0, what="fp32 rtn")
+    # strided views: bf16 with ld = cols + 64, fp32 with ld = cols + 32
+    for dtype, pad in ((torch.bfloat16, 64), (torch.float32, 32)):
+        parent = torch.full((300, 528 + pad), float("inf"), dtype=dtype)
+        parent[:, :528] = f.to(dtype)
+        dv = parent.to(DEV)[:, :528]
+        out = B.quantize(dv, B.SOAR_METHOD_SOAR, 4)
+        torch.cuda.synchronize()
+        host = np_weights(parent)[:, :528]
+        ref = oracle.quantize(host, oracle.METHOD_SOAR, 4)
+        assert np.array_equal(out.codes.cpu().numpy(), ref.codes)
+        assert np.array_equal(out.scales.cpu().numpy(), ref.scales)
+        assert np.float32(out.global_scale.item()) == ref.global_scale
+        assert int(out.status.item()) == 0
+        assert math.isclose(float(B.recon_error(dv, out).item()), ref.sse, rel_tol=REL)
+        back = torch.zeros_like(parent).to(DEV)
+        rc = B.soar_dequantize(out.codes.data_ptr(), out.scales.data_ptr(), out.global_scale.data_ptr(),
+                               300, 528, B.SOAR_BF16 if dtype == torch.bfloat16 else B.SOAR_FP32,
+                               back.data_ptr(), 528 + pad, 0)
+        assert rc == 0
+        torch.cuda.synchronize()
+        want = oracle.dequantize(ref.codes, ref.scales, ref.global_scale,
+                                 oracle.BF16 if dtype == torch.bfloat16 else oracle.FP32)
+        assert np.array_equal(np_weights(back.cpu())[:, :528], want)
+        assert float(back[:, 528:].abs().sum().item()) == 0.0       # padding untouched
+
+
+# ----------------------------------------------------------------- degenerate inputs
+def test_extreme_magnitudes_and_subnormal_scales():
+    g = torch.Generator(device="cpu").manual_seed(9)
+    base = (torch.distributions.StudentT(3.0).sample((128, 256)) * 0.02).float()
+    base[5, 7] = 40.0                      # one huge outlier: most blocks get subnormal/clamped scales
+    base[9, :64] = 1e-9                    # blocks whose codes are all zero
+    base[11, 16:32] = 0.0                  # an all-zero block
+    for k in (0, 100, -100, -112, 60):
+        w = (base * 2.0 ** k).to(torch.bfloat16).to(DEV)
+        for method in (B.SOAR_METHOD_SOAR, B.SOAR_METHOD_RTN):
+            check_against_oracle(w, method, 8, what=f"scale 2^{k} method {method}")
+
+
+def test_all_zero_and_non_finite():
+    z = torch.zeros(33, 64, dtype=torch.bfloat16)
+    z[1, 3] = -0.0
+    out, ref = check_against_oracle(z.to(DEV), B.SOAR_METHOD_SOAR, 4, what="zeros")
+    assert int(out.status.item()) == B.SOAR_STATUS_ALLZERO and out.global_scale.item() == 1.0
+    check_against_oracle(z.to(DEV), B.SOAR_METHOD_RTN, 4, what="zeros rtn")
+    for bad in (float("inf"), float("nan"), float("-inf")):
+        w = torch.randn(40, 160).to(torch.bfloat16)
+        w[7, 99] = bad
+        o = B.quantize(w.to(DEV))
+        torch.cuda.synchronize()
+        assert int(o.status.item()) & B.SOAR_STATUS_NONFINITE
+        s = o.scales.cpu().numpy()
+        assert s.min() >= 1 and s.max() <= 0x7E      # still valid bytes, nothing out of range
+
+
+def test_closed_form_tensor_round_trips_exactly():
+    E2M1 = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+    E4M3 = torch.arange(0, 128, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    rng = np.random.default_rng(17)
+    rows, cols = 96, 512
+    nib = rng.integers(0, 16, size=(rows, cols)).astype(np.uint8)
+    nib[(nib & 7) == 0] = 0
+    dcode = rng.integers(0x08, 0x7F, size=(rows, cols // 16)).astype(np.uint8)
+    dcode[3, 2] = 0x7E
+    nib[:, ::16] = 7
+    q = np.where(nib & 8, -E2M1[nib & 7], E2M1[nib & 7])
+    wv = q * np.repeat(E4M3[dcode], 16, axis=1) * 2.0 ** -6
+    w = torch.from_numpy(wv).to(torch.bfloat16).to(DEV)
+    packed = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    for method in (B.SOAR_METHOD_RTN, B.SOAR_METHOD_SOAR):
+        o = B.quantize(w, method, 4)
+        torch.cuda.synchronize()
+        assert np.array_equal(o.codes.cpu().numpy(), packed)
+        assert np.array_equal(o.scales.cpu().numpy(), dcode)
+        assert o.global_scale.item() == 2.0 ** -6 and o.sse.item() == 0.0
+        assert torch.equal(B.dequantize(o, torch.bfloat16), w)
