@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Throughput of the SOAR NVFP4 hot path on one MI355X.
+
+A "step" is one pass of the whole path (absmax -> Eq. 1-2 statistics -> Eq. 5
+global scale -> Eq. 6 block scales -> Eq. 8 search -> pack) over every tensor of
+the workload, enqueued through the C-ABI batch entry point with the weights
+already resident in HBM.  Default workload: the 36-layer 8B-class decoder
+(252 bf16 tensors, 6.95e9 weights, search radius 4).
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BYTES_3PASS = 6.5625           # per bf16 weight: three reads + codes + scales
+BYTES_SEARCH = 2.5625          # search kernel alone: one read + codes + scales
+BYTES_STATS = 2.0
+BYTES_ABSMAX = 2.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--layers", type=int, default=0, help="workloads 4/5: first N layers only (0 = all)")
+    ap.add_argument("--search", choices=["auto", "full"], default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_12245_amd import binding as B
+    from paper_2605_12245_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B.lib()
+
+    specs = synth.workload_specs(args.workload)
+    per_layer = {4: 7, 5: 3}.get(args.workload, 1)
+    if args.layers and args.workload in (4, 5):
+        specs = specs[: args.layers * per_layer]
+    K = specs[0].dss_radius
+    mode = B.SOAR_SEARCH_AUTO if args.search == "auto" else B.SOAR_SEARCH_FULL
+
+    # ---- resident inputs and outputs
+    t0 = time.time()
+    weights, outs = [], []
+    for s in specs:
+        w = synth.make_weight(s, dev)
+        weights.append(w)
+        outs.append(B.Quantized(torch.empty((s.rows, s.cols // 2), dtype=torch.uint8, device=dev),
+                                torch.empty((s.rows, s.cols // 16), dtype=torch.uint8, device=dev),
+                                torch.empty(1, dtype=torch.float32, device=dev),
+                                torch.empty(1, dtype=torch.float64, device=dev),
+                                torch.empty(1, dtype=torch.int32, device=dev)))
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    E = sum(s.numel for s in specs)
+    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode)
+    ws = B.new_workspace(max(s.rows for s in specs), max(s.cols for s in specs), params, dev)
+    descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+
+    def step():
+        B.quantize_batch(descs, params, ws)
+
+    # ---- timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall0) * 1e3
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    gbs_in = 2.0 * E / (ms_per_step * 1e-3) / 1e9
+
+    sse_soar = sum(float(o.sse.item()) for o in outs)
+    statuses = [int(o.status.item()) for o in outs]
+
+    # ---- per-kernel durations (HIP events on the launch stream), same steps again
+    roofline = None
+    kernels = {}
+    if not args.no_kernel_timing:
+        n_prof = min(args.steps, 5)
+        B.soar_kernel_timing_enable(True)
+        for _ in range(n_prof):
+            step()
+        torch.cuda.synchronize()
+        names = {B.SOAR_KERNEL_INIT: "init", B.SOAR_KERNEL_ABSMAX: "absmax",
+                 B.SOAR_KERNEL_STATS: "stats", B.SOAR_KERNEL_SEARCH: "search"}
+        per_elem = {"absmax": BYTES_ABSMAX, "stats": BYTES_STATS, "search": BYTES_SEARCH, "init": 0.0}
+        for kid, nm in names.items():
+            ms, n = B.soar_kernel_timing_read(kid)
+            kernels[nm] = {"launches": n, "total_ms": ms, "avg_us": (ms / n * 1e3) if n else None,
+                           "ms_per_step": ms / n_prof,
+                           "GBps": (per_elem[nm] * E * n_prof / (ms * 1e-3) / 1e9) if ms > 0 and per_elem[nm] else None}
+        B.soar_kernel_timing_enable(False)
+        dom = max(("absmax", "stats", "search"), key=lambda k: kernels[k]["total_ms"])
+        achieved = kernels[dom]["GBps"]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "bytes_per_weight": per_elem[dom], "avg_launch_us": kernels[dom]["avg_us"]}
+
+    # ---- "MSE vs RTN": the plain max-based NVFP4 of Sec. 3.1 on the same tensors
+    p_rtn = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
+    B.quantize_batch(descs, p_rtn, ws)
+    torch.cuda.synchronize()
+    sse_rtn = sum(float(o.sse.item()) for o in outs)
+
+    # ---- oracle on the host cores, bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        sample = specs[:per_layer] if args.workload in (4, 5) else specs[:1]
+        if args.workload == 5:
+            sample = specs[:1]
+        host = [w.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) for w in weights[: len(sample)]]
+        n_el = sum(s.numel for s in sample)
+        t1 = time.perf_counter()
+        for s, h in zip(sample, host):
+            oracle.quantize(h, oracle.METHOD_SOAR, s.dss_radius)
+        dt = time.perf_counter() - t1
+        cpu = {"value": 2.0 * n_el / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(),
+               "kind": "oracle", "seconds": dt, "weights_per_s": n_el / dt,
+               "sample": f"first {len(sample)} tensor(s) of the workload ({n_el} weights), whole path"}
+
+    out = {
+        "metric": "nvfp4_soar_quantize_throughput",
+        "value": gbs_in,
+        "unit": "GB/s bf16 in",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
+                   "dss_radius": K, "search": args.search, "entry_point": "soar_quantize_batch",
+                   "input": "bf16, resident in HBM"},
+        "weights_per_s": E / (ms_per_step * 1e-3),
+        "hbm_frac_3pass": BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "hbm_frac_single_touch": BYTES_SEARCH * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "mse_vs_rtn": sse_soar / sse_rtn if sse_rtn > 0 else None,
+        "sse_soar": sse_soar, "sse_rtn": sse_rtn,
+        "status_bits_or": int(np_or(statuses)),
+        "wall_ms_per_step": wall_ms / args.steps,
+        "gen_seconds": gen_s,
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def np_or(xs):
+    r = 0
+    for x in xs:
+        r |= x
+    return r
+
+
+if __name__ == "__main__":
+    main()

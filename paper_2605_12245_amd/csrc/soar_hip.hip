@@ -31,20 +31,37 @@
 namespace {
 
 constexpr int kWG = 256;                 // lanes per workgroup = blocks per tile
-constexpr int kMaxPartials = 4096;       // workgroups per reduction kernel, at most
+constexpr int kMaxPartials = 2048;       // workgroups per reduction kernel, at most
+constexpr int kMaxAmaxParts = 1024;      // workgroups of the absmax kernel, at most
+constexpr int kSlots = 64;               // first-level arrival counters
+constexpr int kSlotStride = 32;          // in uint32: one counter per 128 bytes
 constexpr size_t kCtrlBytes = 256;
 constexpr uint32_t kE4M3Min = 0x01u, kE4M3Max = 0x7Eu;
 
+// Control words of one soar_quantize call.  The absmax kernel zeroes the
+// arrival counters; nothing in the workspace needs initialisation by the caller.
 struct Ctrl {
-    uint32_t amax_bits;      // max |w| as binary32 bits (atomicMax)
-    uint32_t ticket_stats;   // workgroups of the stats kernel that have finished
-    uint32_t ticket_search;  // same for the search kernel
-    uint32_t pad;
+    uint32_t top_stats;      // second-level arrival counter of the stats kernel
+    uint32_t top_search;     // same for the search kernel
+    uint32_t amax_bits;      // max |w| as binary32 bits
+    uint32_t n_amax_parts;   // workgroups the absmax kernel ran with
     float    alpha0;
     float    alpha1;
     double   N, M;
 };
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
+
+// Device workspace, carved up by the host.
+struct Workspace {
+    Ctrl     *ctrl;
+    uint32_t *slots_stats;   // kSlots counters, kSlotStride apart
+    uint32_t *slots_search;
+    uint32_t *amax_part;     // kMaxAmaxParts
+    double   *partN, *partM, *partS;   // kMaxPartials each
+};
+constexpr size_t kWorkspaceBytes = kCtrlBytes + 2 * kSlots * kSlotStride * 4 + kMaxAmaxParts * 4 +
+                                   3 * sizeof(double) * (size_t)kMaxPartials;
+static_assert(kWorkspaceBytes % 256 == 0, "workspace size");
 
 struct Geom {
     const void *w;
@@ -183,6 +200,47 @@ __device__ __forceinline__ double wave_pair_tree(double v)
     return v;
 }
 
+// Inter-workgroup hand-off without cache-wide fences.  A workgroup publishes its
+// partial result with agent-scope atomic stores (written through to the point of
+// coherence), waits until they have completed, and then counts itself in with
+// relaxed agent-scope atomics; the workgroup that completes the count reads the
+// partials back with agent-scope atomic loads.  Arrival is counted on two levels
+// (kSlots first-level counters, one top counter) because read-modify-writes on
+// one address serialise at a few tens of nanoseconds each.
+__device__ __forceinline__ void publish(double *p, double v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// called by one lane of the workgroup; true for exactly one workgroup of the grid
+__device__ __forceinline__ bool arrive_is_last(uint32_t *slots, uint32_t *top)
+{
+    const uint32_t G = gridDim.x;
+    const uint32_t ns = G < (uint32_t)kSlots ? G : (uint32_t)kSlots;
+    const uint32_t slot = blockIdx.x % ns;
+    const uint32_t expected = (G - slot + ns - 1) / ns;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);          // the published stores have completed
+    uint32_t t = __hip_atomic_fetch_add(slots + slot * kSlotStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t != expected - 1) return false;
+    uint32_t t2 = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return t2 == ns - 1;
+}
+
+// max over the absmax kernel's per-workgroup results; all lanes must call
+__device__ uint32_t reduce_amax(const uint32_t *part, uint32_t n, uint32_t *lds4)
+{
+    uint32_t m = 0;
+    for (uint32_t k = threadIdx.x; k < n; k += kWG) m = max(m, part[k]);
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = max(max(lds4[0], lds4[1]), max(lds4[2], lds4[3]));
+    __syncthreads();
+    return m;
+}
+
 // tree over the per-workgroup partial sums part[0..P), zero-padded to a power
 // of two; all 256 lanes must call; result valid in every lane
 __device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */)
@@ -217,52 +275,71 @@ __device__ double tree_of_partials(const double *part, uint32_t P, double *lds /
 }
 
 // ------------------------------------------------------------------ kernels
-__global__ void k_init(Ctrl *ctrl)
-{
-    uint32_t *p = reinterpret_cast<uint32_t *>(ctrl);
-    if (threadIdx.x < sizeof(Ctrl) / 4) p[threadIdx.x] = 0u;
-}
-
 // max |w| over a tensor.  |bits| of finite floats order like the values; NaN
 // and Inf patterns are larger than every finite one, so they surface in the max.
+// One partial maximum per workgroup; workgroup 0 also resets the arrival
+// counters of the two kernels that follow on the stream.
+template <int DT>
+__device__ __forceinline__ uint32_t absmax16(uint4 v)
+{
+    if constexpr (DT == SOAR_BF16) {
+        uint32_t a0 = v.x & 0x7FFF7FFFu, a1 = v.y & 0x7FFF7FFFu, a2 = v.z & 0x7FFF7FFFu, a3 = v.w & 0x7FFF7FFFu;
+        uint32_t m = max(max(a0 & 0xFFFFu, a0 >> 16), max(a1 & 0xFFFFu, a1 >> 16));
+        return max(m, max(max(a2 & 0xFFFFu, a2 >> 16), max(a3 & 0xFFFFu, a3 >> 16)));
+    } else {
+        return max(max(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu), max(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu));
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_absmax(const void *w, int64_t rows, int64_t row_chunks,
-                                                int64_t ld_chunks, Ctrl *ctrl)
+                                                int64_t ld_chunks, Workspace ws)
 {
+    __shared__ uint32_t s_wave[4];
     // a "chunk" is 16 bytes; a row holds row_chunks of them, rows are ld_chunks apart
     const uint4 *base = static_cast<const uint4 *>(w);
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        if (tid < kSlots) ws.slots_stats[tid * kSlotStride] = 0u;
+        else if (tid < 2 * kSlots) ws.slots_search[(tid - kSlots) * kSlotStride] = 0u;
+        if (tid == 0) {
+            ws.ctrl->top_stats = 0u;
+            ws.ctrl->top_search = 0u;
+            ws.ctrl->n_amax_parts = gridDim.x * gridDim.y;
+        }
+    }
     uint32_t m = 0;
+    const int64_t stride = (int64_t)gridDim.x * kWG;
     for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
         const uint4 *p = base + r * ld_chunks;
-        for (int64_t c = (int64_t)blockIdx.x * kWG + threadIdx.x; c < row_chunks; c += (int64_t)gridDim.x * kWG) {
-            uint4 v = p[c];
-            if constexpr (DT == SOAR_BF16) {
-                uint32_t a0 = v.x & 0x7FFF7FFFu, a1 = v.y & 0x7FFF7FFFu, a2 = v.z & 0x7FFF7FFFu, a3 = v.w & 0x7FFF7FFFu;
-                m = max(m, max(max(a0 & 0xFFFFu, a0 >> 16), max(a1 & 0xFFFFu, a1 >> 16)));
-                m = max(m, max(max(a2 & 0xFFFFu, a2 >> 16), max(a3 & 0xFFFFu, a3 >> 16)));
-            } else {
-                m = max(m, max(max(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu), max(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu)));
-            }
+        int64_t c = (int64_t)blockIdx.x * kWG + tid;
+        for (; c + 3 * stride < row_chunks; c += 4 * stride) {
+            uint4 v0 = p[c], v1 = p[c + stride], v2 = p[c + 2 * stride], v3 = p[c + 3 * stride];
+            m = max(m, max(max(absmax16<DT>(v0), absmax16<DT>(v1)), max(absmax16<DT>(v2), absmax16<DT>(v3))));
         }
+        for (; c < row_chunks; c += stride) m = max(m, absmax16<DT>(p[c]));
     }
     if constexpr (DT == SOAR_BF16) m <<= 16;
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
-    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&ctrl->amax_bits, m);
+    if ((tid & 63) == 0) s_wave[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0)
+        ws.amax_part[blockIdx.y * gridDim.x + blockIdx.x] = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
 }
 
 // Eq. 1-2 per block and the two tensor-wide sums of Eq. 5
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_stats(Geom g, Ctrl *ctrl, double *partN, double *partM,
-                                               float *d_global_scale)
+__global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_global_scale)
 {
     __shared__ double s_wave[2][4];
     __shared__ double s_stack[2][32];
     __shared__ double s_tree[kWG];
+    __shared__ uint32_t s_u32[4];
     __shared__ uint32_t s_last;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t amax_bits = ctrl->amax_bits;
+    const uint32_t amax_bits = reduce_amax(ws.amax_part, ws.ctrl->n_amax_parts, s_u32);
     const bool degenerate = amax_bits == 0u || amax_bits >= 0x7F800000u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
@@ -303,25 +380,23 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Ctrl *ctrl, double *partN
         __syncthreads();
     }
     if (tid == 0) {
-        partN[blockIdx.x] = wgN;
-        partM[blockIdx.x] = wgM;
-        __threadfence();
-        uint32_t t = __hip_atomic_fetch_add(&ctrl->ticket_stats, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (t == gridDim.x - 1);
+        publish(ws.partN + blockIdx.x, wgN);
+        publish(ws.partM + blockIdx.x, wgM);
+        s_last = arrive_is_last(ws.slots_stats, &ws.ctrl->top_stats) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
     // last workgroup to arrive: finish the trees and apply Eq. 5
-    __threadfence();
-    double N = tree_of_partials(partN, gridDim.x, s_tree);
-    double M = tree_of_partials(partM, gridDim.x, s_tree);
+    double N = tree_of_partials(ws.partN, gridDim.x, s_tree);
+    double M = tree_of_partials(ws.partM, gridDim.x, s_tree);
     if (tid == 0) {
         float alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;
         if (amax_bits == 0u) alpha1 = 1.0f;
-        ctrl->alpha0 = alpha0;
-        ctrl->alpha1 = alpha1;
-        ctrl->N = N;
-        ctrl->M = M;
+        ws.ctrl->amax_bits = amax_bits;
+        ws.ctrl->alpha0 = alpha0;
+        ws.ctrl->alpha1 = alpha1;
+        ws.ctrl->N = N;
+        ws.ctrl->M = M;
         *d_global_scale = alpha1;
     }
 }
@@ -329,20 +404,24 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Ctrl *ctrl, double *partN
 // Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
 // METHOD RTN emits the Eq. 1-2 state instead.
 template <int DT, int METHOD>
-__global__ __launch_bounds__(kWG) void k_search(Geom g, Ctrl *ctrl, int radius, uint8_t *codes, uint8_t *scales,
-                                                double *partS, float *d_global_scale, double *d_sse,
-                                                int32_t *d_status)
+__global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius, uint8_t *codes, uint8_t *scales,
+                                                float *d_global_scale, double *d_sse, int32_t *d_status)
 {
     __shared__ double s_wave[4];
     __shared__ double s_tree[kWG];
+    __shared__ uint32_t s_u32[4];
     __shared__ uint32_t s_last;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t amax_bits = ctrl->amax_bits;
+    uint32_t amax_bits;
+    if constexpr (METHOD == SOAR_METHOD_SOAR)
+        amax_bits = ws.ctrl->amax_bits;                 // left by the stats kernel
+    else
+        amax_bits = reduce_amax(ws.amax_part, ws.ctrl->n_amax_parts, s_u32);
     const bool allzero = amax_bits == 0u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
-    const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? ctrl->alpha1 : alpha0;
+    const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? ws.ctrl->alpha1 : alpha0;
 
     double sse = 0.0;
     const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
@@ -400,15 +479,12 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Ctrl *ctrl, int radius, 
     if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
     __syncthreads();
     if (tid == 0) {
-        partS[blockIdx.x] = (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]);
-        __threadfence();
-        uint32_t t = __hip_atomic_fetch_add(&ctrl->ticket_search, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (t == gridDim.x - 1);
+        publish(ws.partS + blockIdx.x, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
+        s_last = arrive_is_last(ws.slots_search, &ws.ctrl->top_search) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
-    double total = tree_of_partials(partS, gridDim.x, s_tree);
+    double total = tree_of_partials(ws.partS, gridDim.x, s_tree);
     if (tid == 0) {
         if (d_sse) *d_sse = total;
         if (d_status)
@@ -584,52 +660,58 @@ soar_status validate_quantize(const void *d_w, int dtype, int64_t rows, int64_t 
     return SOAR_OK;
 }
 
+Workspace carve(void *d_workspace)
+{
+    char *p = static_cast<char *>(d_workspace);
+    Workspace ws;
+    ws.ctrl = reinterpret_cast<Ctrl *>(p);                 p += kCtrlBytes;
+    ws.slots_stats = reinterpret_cast<uint32_t *>(p);      p += kSlots * kSlotStride * 4;
+    ws.slots_search = reinterpret_cast<uint32_t *>(p);     p += kSlots * kSlotStride * 4;
+    ws.amax_part = reinterpret_cast<uint32_t *>(p);        p += kMaxAmaxParts * 4;
+    ws.partN = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
+    ws.partM = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
+    ws.partS = reinterpret_cast<double *>(p);
+    return ws;
+}
+
 template <int DT>
 soar_status enqueue_quantize(const void *d_w, int64_t rows, int64_t cols, int64_t ld, const soar_params *params,
                              uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale, double *d_sse,
                              int32_t *d_status, void *d_workspace, hipStream_t st)
 {
-    Ctrl *ctrl = static_cast<Ctrl *>(d_workspace);
-    double *partN = reinterpret_cast<double *>(static_cast<char *>(d_workspace) + kCtrlBytes);
-    double *partM = partN + kMaxPartials;
-    double *partS = partM + kMaxPartials;
+    const Workspace ws = carve(d_workspace);
     uint32_t n_wg = 0;
     const Geom g = make_geom(d_w, rows, cols, ld, &n_wg, (uint32_t)params->tiles_per_wg);
     const int64_t es = DT == SOAR_BF16 ? 2 : 4;
-
-    {
-        ScopedTimer t(SOAR_KERNEL_INIT, st);
-        hipLaunchKernelGGL(k_init, dim3(1), dim3(64), 0, st, ctrl);
-        SOAR_LAUNCH_CHECK();
-    }
     {
         ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
         int64_t a_rows = rows, row_chunks = cols * es / 16, ld_chunks = ld * es / 16;
         if (ld == cols) { row_chunks *= rows; a_rows = 1; ld_chunks = row_chunks; }
-        int64_t gx = (row_chunks + (int64_t)kWG * 4 - 1) / ((int64_t)kWG * 4);
-        if (gx > 2048) gx = 2048;
+        // about 8 chunks per lane, at most kMaxAmaxParts workgroups in all
+        int64_t gx = (row_chunks + (int64_t)kWG * 8 - 1) / ((int64_t)kWG * 8);
+        if (gx > kMaxAmaxParts) gx = kMaxAmaxParts;
         if (gx < 1) gx = 1;
         int64_t gy = a_rows;
-        const int64_t gy_cap = (4096 + gx - 1) / gx;
+        const int64_t gy_cap = kMaxAmaxParts / gx;
         if (gy > gy_cap) gy = gy_cap;
         hipLaunchKernelGGL(k_absmax<DT>, dim3((uint32_t)gx, (uint32_t)gy), dim3(kWG), 0, st, d_w, a_rows,
-                           row_chunks, ld_chunks, ctrl);
+                           row_chunks, ld_chunks, ws);
         SOAR_LAUNCH_CHECK();
     }
     if (params->method == SOAR_METHOD_SOAR) {
         {
             ScopedTimer t(SOAR_KERNEL_STATS, st);
-            hipLaunchKernelGGL(k_stats<DT>, dim3(n_wg), dim3(kWG), 0, st, g, ctrl, partN, partM, d_global_scale);
+            hipLaunchKernelGGL(k_stats<DT>, dim3(n_wg), dim3(kWG), 0, st, g, ws, d_global_scale);
             SOAR_LAUNCH_CHECK();
         }
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(n_wg), dim3(kWG), 0, st, g, ctrl,
-                           params->dss_radius, d_codes, d_scales, partS, d_global_scale, d_sse, d_status);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(n_wg), dim3(kWG), 0, st, g, ws,
+                           params->dss_radius, d_codes, d_scales, d_global_scale, d_sse, d_status);
         SOAR_LAUNCH_CHECK();
     } else {
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ctrl, 0, d_codes,
-                           d_scales, partS, d_global_scale, d_sse, d_status);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ws, 0, d_codes,
+                           d_scales, d_global_scale, d_sse, d_status);
         SOAR_LAUNCH_CHECK();
     }
     return SOAR_OK;
@@ -659,7 +741,7 @@ void soar_default_params(soar_params *p)
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)
 {
     if (!valid_params(params) || check_shape(rows, cols, cols) != SOAR_OK) return 0;
-    return kCtrlBytes + 3 * sizeof(double) * (size_t)kMaxPartials;
+    return kWorkspaceBytes;
 }
 
 soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
