@@ -58,10 +58,11 @@ struct Workspace {
     uint32_t *slots_search;
     uint32_t *amax_part;     // kMaxAmaxParts
     double   *partN, *partM, *partS;   // kMaxPartials each
+    float2   *ab;            // one per block: the block sums of the Eq. 1-2 state
 };
-constexpr size_t kWorkspaceBytes = kCtrlBytes + 2 * kSlots * kSlotStride * 4 + kMaxAmaxParts * 4 +
-                                   3 * sizeof(double) * (size_t)kMaxPartials;
-static_assert(kWorkspaceBytes % 256 == 0, "workspace size");
+constexpr size_t kFixedWorkspaceBytes = kCtrlBytes + 2 * kSlots * kSlotStride * 4 + kMaxAmaxParts * 4 +
+                                        3 * sizeof(double) * (size_t)kMaxPartials;
+static_assert(kFixedWorkspaceBytes % 256 == 0, "workspace size");
 
 struct Geom {
     const void *w;
@@ -193,11 +194,35 @@ __device__ __forceinline__ void block_init(const float w[16], float alpha0, floa
 }
 
 // ------------------------------------------------------------------ reductions
+// Adjacent-pair tree over the 64 lanes of a wave; the result is uniform.
+// Inside a row of 16 lanes the partner values come through DPP (lane^1, lane^2,
+// then the mirrored half-row and row, whose lanes already hold equal sums);
+// the four row sums are combined as (r0+r1)+(r2+r3).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
 __device__ __forceinline__ double wave_pair_tree(double v)
 {
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) v = v + __shfl_xor(v, s, 64);
-    return v;
+    v = v + dpp_f64<0xB1>(v);      // quad_perm [1,0,3,2]
+    v = v + dpp_f64<0x4E>(v);      // quad_perm [2,3,0,1]
+    v = v + dpp_f64<0x141>(v);     // row_half_mirror
+    v = v + dpp_f64<0x140>(v);     // row_mirror
+    const double r0 = readlane_f64(v, 0), r1 = readlane_f64(v, 16);
+    const double r2 = readlane_f64(v, 32), r3 = readlane_f64(v, 48);
+    return (r0 + r1) + (r2 + r3);
 }
 
 // Inter-workgroup hand-off without cache-wide fences.  A workgroup publishes its
@@ -245,22 +270,23 @@ __device__ uint32_t reduce_amax(const uint32_t *part, uint32_t n, uint32_t *lds4
 // of two; all 256 lanes must call; result valid in every lane
 __device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */)
 {
+    constexpr int kPerLane = kMaxPartials / kWG;
     uint32_t P2 = 1;
     while (P2 < P) P2 <<= 1;
-    const uint32_t C = P2 > (uint32_t)kWG ? P2 / kWG : 1;     // <= 16
+    const uint32_t C = P2 > (uint32_t)kWG ? P2 / kWG : 1;     // <= kPerLane
     const uint32_t tid = threadIdx.x;
-    double v[16];
+    double v[kPerLane];
 #pragma unroll
-    for (uint32_t k = 0; k < 16; ++k) {
+    for (uint32_t k = 0; k < (uint32_t)kPerLane; ++k) {
         uint32_t idx = tid * C + k;
         v[k] = (k < C && idx < P)
                    ? __hip_atomic_load(part + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                    : 0.0;
     }
 #pragma unroll
-    for (int s = 1; s < 16; s <<= 1)
+    for (int s = 1; s < kPerLane; s <<= 1)
 #pragma unroll
-        for (int k = 0; k < 16; k += 2 * s) v[k] = v[k] + v[k + s];
+        for (int k = 0; k < kPerLane; k += 2 * s) v[k] = v[k] + v[k + s];
     __syncthreads();
     lds[tid] = v[0];
     __syncthreads();
@@ -328,10 +354,18 @@ __global__ __launch_bounds__(kWG) void k_absmax(const void *w, int64_t rows, int
         ws.amax_part[blockIdx.y * gridDim.x + blockIdx.x] = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
 }
 
-// Eq. 1-2 per block and the two tensor-wide sums of Eq. 5
+// Eq. 1-2 per block and the two tensor-wide sums of Eq. 5.  The per-block terms
+// of kStage consecutive tiles are staged in LDS; lane t then folds the kStage
+// adjacent terms t*kStage.. in registers and one wave tree finishes the group,
+// which is the same adjacent-pair tree at a fraction of the cross-lane work.
+// Each block's (a, b) -- or (Delta0, 0) when its codes are all zero -- is kept
+// for the search kernel.
+constexpr int kStage = 4;
+
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_global_scale)
 {
+    __shared__ double2 s_terms[kStage * kWG];
     __shared__ double s_wave[2][4];
     __shared__ double s_stack[2][32];
     __shared__ double s_tree[kWG];
@@ -346,27 +380,51 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_gl
 
     double wgN = 0.0, wgM = 0.0;
     const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
-    for (uint32_t k = 0; k < g.tiles_per_wg; ++k) {
-        const uint32_t i = (tile0 + k) * kWG + tid;
-        double tN = 0.0, tM = 0.0;
-        if (i < g.nblk && !degenerate) {
-            float w[16], q[16];
-            uint32_t nib[2], c0;
-            float delta0, a, b;
-            load_block<DT>(g.w, block_offset(g, i), w);
-            block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
-            block_sums(w, q, a, b);
-            tN = (double)a * (double)delta0;
-            tM = ((double)b * (double)delta0) * (double)delta0;
+    const uint32_t T = g.tiles_per_wg < (uint32_t)kStage ? g.tiles_per_wg : (uint32_t)kStage;   // power of two
+    for (uint32_t kg = 0; kg < g.tiles_per_wg; kg += T) {
+        for (uint32_t kk = 0; kk < T; ++kk) {
+            const uint32_t i = (tile0 + kg + kk) * kWG + tid;
+            double tN = 0.0, tM = 0.0;
+            if (i < g.nblk) {
+                float a = 0.0f, b = 0.0f;
+                if (!degenerate) {
+                    float w[16], q[16];
+                    uint32_t nib[2], c0;
+                    float delta0;
+                    load_block<DT>(g.w, block_offset(g, i), w);
+                    block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                    block_sums(w, q, a, b);
+                    tN = (double)a * (double)delta0;
+                    tM = ((double)b * (double)delta0) * (double)delta0;
+                    if (b == 0.0f) a = delta0;
+                }
+                ws.ab[i] = make_float2(a, b);
+            }
+            s_terms[kk * kWG + tid] = make_double2(tN, tM);
         }
-        tN = wave_pair_tree(tN);
-        tM = wave_pair_tree(tM);
-        if ((tid & 63) == 0) { s_wave[0][tid >> 6] = tN; s_wave[1][tid >> 6] = tM; }
+        __syncthreads();
+        double vN, vM;
+        {
+            double2 t0 = s_terms[tid * T];
+            vN = t0.x; vM = t0.y;
+            if (T >= 2) {
+                double2 t1 = s_terms[tid * T + 1];
+                vN = vN + t1.x; vM = vM + t1.y;
+            }
+            if (T == 4) {
+                double2 t2 = s_terms[tid * T + 2], t3 = s_terms[tid * T + 3];
+                vN = vN + (t2.x + t3.x); vM = vM + (t2.y + t3.y);
+            }
+        }
+        vN = wave_pair_tree(vN);
+        vM = wave_pair_tree(vM);
+        if ((tid & 63) == 0) { s_wave[0][tid >> 6] = vN; s_wave[1][tid >> 6] = vM; }
         __syncthreads();
         if (tid == 0) {
-            // tile sum, then binary-counter stack: tile k closes every level whose bit of k is set
-            double vN = (s_wave[0][0] + s_wave[0][1]) + (s_wave[0][2] + s_wave[0][3]);
-            double vM = (s_wave[1][0] + s_wave[1][1]) + (s_wave[1][2] + s_wave[1][3]);
+            // group sum, then binary-counter stack: group k closes every level whose bit of k is set
+            vN = (s_wave[0][0] + s_wave[0][1]) + (s_wave[0][2] + s_wave[0][3]);
+            vM = (s_wave[1][0] + s_wave[1][1]) + (s_wave[1][2] + s_wave[1][3]);
+            const uint32_t k = kg / T;
             uint32_t lvl = 0;
             while ((k >> lvl) & 1u) {
                 vN = s_stack[0][lvl] + vN;
@@ -375,9 +433,8 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_gl
             }
             s_stack[0][lvl] = vN;
             s_stack[1][lvl] = vM;
-            wgN = vN; wgM = vM;          // after the last tile: the sum of all tiles
+            wgN = vN; wgM = vM;          // after the last group: the sum of all tiles
         }
-        __syncthreads();
     }
     if (tid == 0) {
         publish(ws.partN + blockIdx.x, wgN);
@@ -401,11 +458,81 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_gl
     }
 }
 
+// Exhaustive form of the Eq. 8 search: candidates centre, -1, +1, -2, +2, ...;
+// a later one wins only if strictly better.  A code outside [0x01, 0x7E] is
+// clamped onto an already evaluated candidate and can then never win.
+__device__ __forceinline__ void search_full(const float w[16], const float q[16], float alpha1, int centre,
+                                            int radius, int &best, float &best_err)
+{
+    best = centre;
+    best_err = block_error(w, q, alpha1 * e4m3_value((uint32_t)centre));
+    for (int o = 1; o <= radius; ++o) {
+        int cm = max(centre - o, (int)kE4M3Min);
+        float em = block_error(w, q, alpha1 * e4m3_value((uint32_t)cm));
+        if (em < best_err) { best_err = em; best = cm; }
+        int cp = min(centre + o, (int)kE4M3Max);
+        float ep = block_error(w, q, alpha1 * e4m3_value((uint32_t)cp));
+        if (ep < best_err) { best_err = ep; best = cp; }
+    }
+}
+
+// position of a candidate in the search order 0,-1,+1,-2,+2,...
+__device__ __forceinline__ int search_rank(int code, int centre)
+{
+    const int o = code - centre;
+    return o < 0 ? -2 * o - 1 : 2 * o;
+}
+
+// Certified short form of the same search.  For fixed codes the exact block
+// error is a parabola in s = alpha*d, f(s) = A - 2Bs + Cs^2, with minimiser
+// s* = B/C (B = sum w q, C = sum q^2).  The two window candidates that bracket
+// s* are evaluated with the very same binary32 chain as the exhaustive search;
+// their winner is the exhaustive winner provided that
+//   (i)  the bracket really encloses s* (checked with a margin far above the
+//        rounding error of the computed B/C), so that f rises monotonically
+//        through every other candidate on either side, and
+//   (ii) that rise, at least C*h^2 with h the E4M3 spacing (>= s/16), exceeds the
+//        worst-case rounding error of the binary32 evaluation (18 ulp relative,
+//        all terms being non-negative), so no unevaluated candidate can compute
+//        to a value as small as the winner's.
+// Returns false when a condition cannot be shown; the caller then runs the
+// exhaustive search, so the result never depends on this shortcut.
+__device__ __forceinline__ bool search_certified(const float w[16], const float q[16], float alpha1,
+                                                 float inv_alpha1, int centre, int radius, int &best,
+                                                 float &best_err)
+{
+    float B, C;
+    block_sums(w, q, B, C);
+    const int wmin = max(centre - radius, (int)kE4M3Min);
+    const int wmax = min(centre + radius, (int)kE4M3Max);
+    const float sstar = B * __builtin_amdgcn_rcpf(C);
+    const float dstar = sstar * inv_alpha1;
+    // largest E4M3 code whose value does not exceed dstar (approximately; (i) checks)
+    const int lo_n = (int)(__float_as_uint(dstar) >> 20) - (120 << 3);
+    const int lo_s = (int)(dstar * 512.0f);
+    const int lo = dstar >= 0x1p-6f ? lo_n : lo_s;
+    const int ka = min(max(lo, wmin), wmax);
+    const int kb = min(max(lo + 1, wmin), wmax);
+    const float sa = alpha1 * e4m3_value((uint32_t)ka);
+    const float sb = alpha1 * e4m3_value((uint32_t)kb);
+    const float fa = block_error(w, q, sa);
+    const float fb = block_error(w, q, sb);
+    const bool b_wins = (fb < fa) || (fb == fa && search_rank(kb, centre) < search_rank(ka, centre));
+    best = b_wins ? kb : ka;
+    best_err = b_wins ? fb : fa;
+    const bool left_ok = (ka == wmin) || (sa * (1.0f + 0x1p-17f) <= sstar);
+    const bool right_ok = (kb == wmax) || (sb * (1.0f - 0x1p-17f) >= sstar);
+    const bool margin_ok = best_err < 512.0f * (C * (sa * sa));
+    const bool range_ok = (B > 0x1p-100f) && (best_err > 0x1p-100f) && (C > 0.0f);
+    return left_ok && right_ok && margin_ok && range_ok;
+}
+
 // Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
 // METHOD RTN emits the Eq. 1-2 state instead.
 template <int DT, int METHOD>
-__global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius, uint8_t *codes, uint8_t *scales,
-                                                float *d_global_scale, double *d_sse, int32_t *d_status)
+__global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius, int full_search,
+                                                uint8_t *codes, uint8_t *scales, float *d_global_scale,
+                                                double *d_sse, int32_t *d_status)
 {
     __shared__ double s_wave[4];
     __shared__ double s_tree[kWG];
@@ -422,6 +549,7 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
     const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? ws.ctrl->alpha1 : alpha0;
+    const float inv_alpha1 = __builtin_amdgcn_rcpf(alpha1);
 
     double sse = 0.0;
     const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
@@ -429,8 +557,7 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius
         const uint32_t i = (tile0 + k) * kWG + tid;
         if (i >= g.nblk) continue;
         float w[16], q[16];
-        uint32_t nib[2], c0;
-        float delta0;
+        uint32_t nib[2];
         load_block<DT>(g.w, block_offset(g, i), w);
         uint32_t out_code;
         float out_err;
@@ -443,32 +570,24 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius
             nib[1] = fp4x8(x + 8);
             out_code = kE4M3Min;
             out_err = 0.0f;
-        } else {
+        } else if constexpr (METHOD == SOAR_METHOD_RTN) {
+            uint32_t c0;
+            float delta0;
             block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
-            if constexpr (METHOD == SOAR_METHOD_RTN) {
-                out_code = c0;
-                out_err = block_error(w, q, alpha0 * delta0);
-            } else {
-                float a, b;
-                block_sums(w, q, a, b);
-                const float delta_star = (b == 0.0f) ? delta0 : a / (alpha1 * b);
-                const int centre = (int)e4m3_project(delta_star);
-                assign_codes(w, alpha1 * delta_star, nib, q);
-                int best = centre;
-                float best_err = block_error(w, q, alpha1 * e4m3_value((uint32_t)centre));
-                for (int o = 1; o <= radius; ++o) {
-                    // a code outside [0x01, 0x7E] is clamped onto an already evaluated
-                    // candidate and can then never be strictly better
-                    int cm = max(centre - o, (int)kE4M3Min);
-                    float em = block_error(w, q, alpha1 * e4m3_value((uint32_t)cm));
-                    if (em < best_err) { best_err = em; best = cm; }
-                    int cp = min(centre + o, (int)kE4M3Max);
-                    float ep = block_error(w, q, alpha1 * e4m3_value((uint32_t)cp));
-                    if (ep < best_err) { best_err = ep; best = cp; }
-                }
-                out_code = (uint32_t)best;
-                out_err = best_err;
-            }
+            out_code = c0;
+            out_err = block_error(w, q, alpha0 * delta0);
+        } else {
+            const float2 ab = ws.ab[i];       // (a, b), or (Delta0, 0)
+            const float delta_star = (ab.y == 0.0f) ? ab.x : ab.x / (alpha1 * ab.y);
+            const int centre = (int)e4m3_project(delta_star);
+            assign_codes(w, alpha1 * delta_star, nib, q);
+            int best;
+            float best_err;
+            bool done = false;
+            if (!full_search) done = search_certified(w, q, alpha1, inv_alpha1, centre, radius, best, best_err);
+            if (!done) search_full(w, q, alpha1, centre, radius, best, best_err);
+            out_code = (uint32_t)best;
+            out_err = best_err;
         }
         reinterpret_cast<uint2 *>(codes)[i] = make_uint2(nib[0], nib[1]);
         scales[i] = (uint8_t)out_code;
@@ -670,7 +789,8 @@ Workspace carve(void *d_workspace)
     ws.amax_part = reinterpret_cast<uint32_t *>(p);        p += kMaxAmaxParts * 4;
     ws.partN = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
     ws.partM = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
-    ws.partS = reinterpret_cast<double *>(p);
+    ws.partS = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
+    ws.ab = reinterpret_cast<float2 *>(p);
     return ws;
 }
 
@@ -706,11 +826,12 @@ soar_status enqueue_quantize(const void *d_w, int64_t rows, int64_t cols, int64_
         }
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
         hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(n_wg), dim3(kWG), 0, st, g, ws,
-                           params->dss_radius, d_codes, d_scales, d_global_scale, d_sse, d_status);
+                           params->dss_radius, params->search_mode == SOAR_SEARCH_FULL ? 1 : 0, d_codes,
+                           d_scales, d_global_scale, d_sse, d_status);
         SOAR_LAUNCH_CHECK();
     } else {
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ws, 0, d_codes,
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ws, 0, 1, d_codes,
                            d_scales, d_global_scale, d_sse, d_status);
         SOAR_LAUNCH_CHECK();
     }
@@ -741,7 +862,8 @@ void soar_default_params(soar_params *p)
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)
 {
     if (!valid_params(params) || check_shape(rows, cols, cols) != SOAR_OK) return 0;
-    return kWorkspaceBytes;
+    const size_t per_block = sizeof(float2) * (size_t)(rows * (cols / 16));
+    return kFixedWorkspaceBytes + ((per_block + 255) / 256) * 256;
 }
 
 soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
