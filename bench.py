@@ -79,8 +79,8 @@ def main():
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
     params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode)
-    ws = B.new_workspace(max(s.rows for s in specs), max(s.cols for s in specs), params, dev)
     descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+    ws = B.new_batch_workspace(descs, params, dev)
 
     def step():
         B.quantize_batch(descs, params, ws)

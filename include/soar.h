@@ -85,9 +85,11 @@ void soar_default_params(soar_params *p);
 
 /*
  * Bytes of device workspace soar_quantize needs for a rows x cols tensor
- * (control words and per-workgroup partial sums of the tensor-wide reductions).
- * The workspace must be 256-byte aligned; its contents need no initialisation
- * and are undefined afterwards.  Returns 0 on a bad argument.
+ * (control words, per-workgroup partial sums of the tensor-wide reductions of
+ * Eq. 5, and 6 bytes per block for the block sums carried from the statistics
+ * pass to the search pass).  The workspace must be 256-byte aligned; its
+ * contents need no initialisation and are undefined afterwards.  Returns 0 on a
+ * bad argument.
  */
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params);
 
@@ -134,13 +136,20 @@ typedef struct {
 
 /*
  * soar_quantize_batch -- soar_quantize for n tensors (the linear layers of a
- * model, Sec. 4.1), enqueued back to back on one stream with one shared
- * workspace of at least the largest soar_workspace_bytes() of its members.
- * `descs` is HOST memory and is not referenced after the call returns.  All
- * descriptors are validated before anything is enqueued.
+ * model, Sec. 4.1) on one stream with one shared workspace of at least
+ * soar_batch_workspace_bytes().  Consecutive tensors of one element type are
+ * served by the same kernel launches (up to 8 tensors and 2^28 weights per
+ * launch), each tensor with its own tensor-wide reductions; results are those
+ * of n separate soar_quantize calls.  `descs` is HOST memory and is not
+ * referenced after the call returns.  All descriptors are validated before
+ * anything is enqueued.
  */
 soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params,
                                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Workspace bytes soar_quantize_batch needs for these n tensors (0 on a bad
+ * argument).  Only shapes and element types of the descriptors are read. */
+size_t soar_batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs, const soar_params *params);
 
 /*
  * soar_dequantize -- Eq. 3: w^_ij = q_ij * (alpha * d_i), the product alpha*d_i

@@ -23,7 +23,8 @@ SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO = 1, 2
  SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_COUNT) = range(7)
 
 EXPORTS = (
-    "soar_default_params", "soar_workspace_bytes", "soar_quantize", "soar_quantize_batch",
+    "soar_default_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
+    "soar_quantize_batch",
     "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
 )
@@ -73,6 +74,8 @@ def lib():
     L.soar_default_params.restype = None
     L.soar_workspace_bytes.argtypes = [i64, i64, C.POINTER(soar_params)]
     L.soar_workspace_bytes.restype = C.c_size_t
+    L.soar_batch_workspace_bytes.argtypes = [i32, C.POINTER(soar_tensor_desc), C.POINTER(soar_params)]
+    L.soar_batch_workspace_bytes.restype = C.c_size_t
     L.soar_quantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_params), vp, vp, vp, vp, vp,
                                 vp, C.c_size_t, vp]
     L.soar_quantize.restype = i32
@@ -113,6 +116,11 @@ def soar_default_params(method: int = SOAR_METHOD_SOAR, dss_radius: int = 4,
 
 def soar_workspace_bytes(rows: int, cols: int, params: soar_params) -> int:
     return int(lib().soar_workspace_bytes(rows, cols, C.byref(params)))
+
+
+def soar_batch_workspace_bytes(descs: Sequence[soar_tensor_desc], params: soar_params) -> int:
+    arr = (soar_tensor_desc * len(descs))(*descs)
+    return int(lib().soar_batch_workspace_bytes(len(descs), arr, C.byref(params)))
 
 
 def soar_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
@@ -200,6 +208,13 @@ def new_workspace(rows: int, cols: int, params: soar_params, device) -> torch.Te
     n = soar_workspace_bytes(rows, cols, params)
     if n == 0:
         raise SoarError(2, "soar_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def new_batch_workspace(descs: Sequence[soar_tensor_desc], params: soar_params, device) -> torch.Tensor:
+    n = soar_batch_workspace_bytes(descs, params)
+    if n == 0:
+        raise SoarError(2, "soar_batch_workspace_bytes")
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 

@@ -1,21 +1,25 @@
 // SOAR NVFP4 weight quantization for MI355X (gfx950): HIP kernels and C-ABI.
 //
-// Path (arXiv 2605.12245, Algorithm 1 with T = 1 and beta = 1):
-//   absmax kernel   max|W|                      -> alpha0            (Eq. 1)
-//   stats kernel    per block: Delta0, Q0, a=sum wq, b=sum q^2       (Eq. 1-2)
-//                   tensor:    N=sum a*Delta0, M=sum b*Delta0^2      (Eq. 5)
-//                   last workgroup: alpha1 = N/M
-//   search kernel   per block: Delta* = a/(alpha1 b) (Eq. 6), centre = E4M3(Delta*)
-//                   (Appendix D), Q1 = Q_FP4(W/(alpha1 Delta*)), search of the
-//                   stored scale over centre-K..centre+K by Eq. 8, pack, error sum
+// Path (arXiv 2605.12245, Algorithm 1 with T = 1 and beta = 1), three streaming
+// kernels per group of tensors:
+//   absmax   max|W|                                     -> alpha0       (Eq. 1)
+//   stats    per block: Delta0, Q0, a = sum w q, b = sum q^2            (Eq. 1-2)
+//            tensor:    N = sum a Delta0, M = sum b Delta0^2 -> alpha1  (Eq. 5)
+//   search   per block: Delta* = a/(alpha1 b) (Eq. 6), centre = E4M3(Delta*)
+//            (Appendix D), Q1 = Q_FP4(W/(alpha1 Delta*)), search of the stored
+//            scale over centre-K..centre+K by Eq. 8, pack, error sum
 //
 // Work decomposition: one lane owns one 16-element block (two 128-bit loads for
-// bf16), so every per-block reduction is a register chain and no cross-lane
-// traffic is needed on the per-element path.  A workgroup of 256 lanes owns a
-// "tile" of 256 consecutive blocks.  The two tensor-wide sums are binary64
-// adjacent-pair trees over the flat block index; a wave butterfly, a 4-wave LDS
-// step and a binary-counter stack per workgroup reproduce that tree exactly for
-// any power-of-two number of tiles per workgroup.
+// bf16), so every per-block reduction is a register chain with no cross-lane
+// traffic.  A workgroup of 256 lanes owns "tiles" of 256 consecutive blocks.
+// The two tensor-wide sums are binary64 adjacent-pair trees over the flat block
+// index: LDS staging of a few tiles, a DPP wave tree, a 4-wave step and a
+// binary-counter stack reproduce that tree exactly for any power-of-two number
+// of tiles per workgroup.  One launch serves up to kGroupMax tensors (each with
+// its own range of workgroups) so that small tensors do not pay a launch each.
+//
+// Tensor-wide results are finished by the last workgroup of a tensor to arrive
+// (two-level arrival counters, no spinning, no cache-wide fences).
 //
 // Build: hipcc --offload-arch=gfx950 -O3 -ffp-contract=off (no fast-math): every
 // float operation below is a separate IEEE binary32 operation unless written as
@@ -31,47 +35,65 @@
 namespace {
 
 constexpr int kWG = 256;                 // lanes per workgroup = blocks per tile
-constexpr int kMaxPartials = 2048;       // workgroups per reduction kernel, at most
-constexpr int kMaxAmaxParts = 1024;      // workgroups of the absmax kernel, at most
+constexpr int kStage = 4;                // tiles whose block terms are staged in LDS per tree step
+constexpr int kMaxPartials = 16384;      // workgroups per tensor, at most
+constexpr int kGroupMax = 8;             // tensors per launch
+constexpr int64_t kGroupElemCap = (int64_t)1 << 28;   // weights per launch (beyond the first tensor)
 constexpr int kSlots = 64;               // first-level arrival counters
 constexpr int kSlotStride = 32;          // in uint32: one counter per 128 bytes
-constexpr size_t kCtrlBytes = 256;
+constexpr int kKernels = 3;              // absmax, stats, search
 constexpr uint32_t kE4M3Min = 0x01u, kE4M3Max = 0x7Eu;
 
-// Control words of one soar_quantize call.  The absmax kernel zeroes the
-// arrival counters; nothing in the workspace needs initialisation by the caller.
+// Control words of one tensor slot.  soar_quantize* zeroes them once per call;
+// after that every kernel leaves its own counters at zero again.
 struct Ctrl {
-    uint32_t top_stats;      // second-level arrival counter of the stats kernel
-    uint32_t top_search;     // same for the search kernel
+    uint32_t top[4];         // second-level arrival counter of each kernel
     uint32_t amax_bits;      // max |w| as binary32 bits
-    uint32_t n_amax_parts;   // workgroups the absmax kernel ran with
     float    alpha0;
     float    alpha1;
+    uint32_t pad;
     double   N, M;
 };
+constexpr size_t kCtrlBytes = 256;
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
+constexpr size_t kCountersBytes = (size_t)kKernels * kSlots * kSlotStride * 4;
+constexpr size_t kSlotMaxBytes = (size_t)kSlots * kSlotStride * 4;
+constexpr size_t kZeroedBytes = kCtrlBytes + kCountersBytes + kSlotMaxBytes;   // what k_init clears
+constexpr size_t kPartialsBytes = 3 * sizeof(double) * (size_t)kMaxPartials;
+constexpr size_t kSlotBytes = kZeroedBytes + kPartialsBytes;                   // per tensor slot
+static_assert(kSlotBytes % 256 == 0, "slot size");
 
-// Device workspace, carved up by the host.
-struct Workspace {
-    Ctrl     *ctrl;
-    uint32_t *slots_stats;   // kSlots counters, kSlotStride apart
-    uint32_t *slots_search;
-    uint32_t *amax_part;     // kMaxAmaxParts
-    double   *partN, *partM, *partS;   // kMaxPartials each
-    float2   *ab;            // one per block: the block sums of the Eq. 1-2 state
-};
-constexpr size_t kFixedWorkspaceBytes = kCtrlBytes + 2 * kSlots * kSlotStride * 4 + kMaxAmaxParts * 4 +
-                                        3 * sizeof(double) * (size_t)kMaxPartials;
-static_assert(kFixedWorkspaceBytes % 256 == 0, "workspace size");
-
-struct Geom {
+// One tensor of a launch.
+struct Task {
     const void *w;
+    uint8_t  *codes, *scales;
+    float    *gscale;
+    double   *sse;
+    int32_t  *status;
     int64_t  ld;             // leading dimension, elements
     uint32_t bpr;            // blocks per row
     uint32_t nblk;           // blocks in the tensor
     uint32_t tiles_per_wg;   // power of two
     uint32_t contiguous;     // ld == cols
+    uint32_t wg_begin;       // first workgroup of the grid that works on this tensor
+    uint32_t n_wg;           // how many do
+    // workspace of the slot
+    Ctrl     *ctrl;
+    uint32_t *counters;      // [kKernels][kSlots] arrival counters, kSlotStride apart
+    uint32_t *slot_max;      // [kSlots] partial maxima of the absmax kernel, kSlotStride apart
+    double   *part;          // [3][kMaxPartials] partial sums N, M, error
+    float    *a;             // [nblk] block sum a (or Delta0 where b == 0)
+    uint16_t *b4;            // [nblk] 4 * block sum b (an integer <= 2304)
 };
+
+struct Batch {
+    Task     t[kGroupMax];
+    uint32_t n;
+    int32_t  radius;
+    int32_t  full_search;
+};
+
+typedef Task Geom;           // the addressing fields are all block_offset needs
 
 // ------------------------------------------------------------------ formats
 __device__ __forceinline__ float f_of(uint32_t u) { return __uint_as_float(u); }
@@ -225,86 +247,114 @@ __device__ __forceinline__ double wave_pair_tree(double v)
     return (r0 + r1) + (r2 + r3);
 }
 
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t m)
+{
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
+    return m;
+}
+
 // Inter-workgroup hand-off without cache-wide fences.  A workgroup publishes its
-// partial result with agent-scope atomic stores (written through to the point of
-// coherence), waits until they have completed, and then counts itself in with
-// relaxed agent-scope atomics; the workgroup that completes the count reads the
-// partials back with agent-scope atomic loads.  Arrival is counted on two levels
-// (kSlots first-level counters, one top counter) because read-modify-writes on
-// one address serialise at a few tens of nanoseconds each.
+// partial result with agent-scope atomics (performed at the point of coherence),
+// waits until they have completed, and then counts itself in with relaxed
+// agent-scope atomics; the workgroup that completes the count reads the partials
+// back with agent-scope atomic loads.  Arrival is counted on two levels (kSlots
+// first-level counters, one top counter) because read-modify-writes on a single
+// address serialise at roughly ten nanoseconds each.
 __device__ __forceinline__ void publish(double *p, double v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// called by one lane of the workgroup; true for exactly one workgroup of the grid
-__device__ __forceinline__ bool arrive_is_last(uint32_t *slots, uint32_t *top)
+// called by one lane of the workgroup; true for exactly one of the tensor's G workgroups
+__device__ __forceinline__ bool arrive_is_last(uint32_t *slots, uint32_t *top, uint32_t G, uint32_t lwg)
 {
-    const uint32_t G = gridDim.x;
     const uint32_t ns = G < (uint32_t)kSlots ? G : (uint32_t)kSlots;
-    const uint32_t slot = blockIdx.x % ns;
+    const uint32_t slot = lwg % ns;
     const uint32_t expected = (G - slot + ns - 1) / ns;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);          // the published stores have completed
+    __builtin_amdgcn_s_waitcnt(0);          // what this lane published has completed
     uint32_t t = __hip_atomic_fetch_add(slots + slot * kSlotStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (t != expected - 1) return false;
     uint32_t t2 = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return t2 == ns - 1;
 }
 
-// max over the absmax kernel's per-workgroup results; all lanes must call
-__device__ uint32_t reduce_amax(const uint32_t *part, uint32_t n, uint32_t *lds4)
+// the last workgroup puts the counters back to zero for the next launch
+__device__ __forceinline__ void reset_counters(uint32_t *slots, uint32_t *top)
 {
-    uint32_t m = 0;
-    for (uint32_t k = threadIdx.x; k < n; k += kWG) m = max(m, part[k]);
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
-    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = m;
-    __syncthreads();
-    m = max(max(lds4[0], lds4[1]), max(lds4[2], lds4[3]));
-    __syncthreads();
-    return m;
+    if (threadIdx.x < kSlots) slots[threadIdx.x * kSlotStride] = 0u;
+    if (threadIdx.x == 0) *top = 0u;
 }
 
-// tree over the per-workgroup partial sums part[0..P), zero-padded to a power
-// of two; all 256 lanes must call; result valid in every lane
-__device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */)
+// Adjacent-pair tree over the per-workgroup partial sums part[0..P), zero-padded
+// to a power of two.  All lanes of the workgroup must call; the result is valid
+// in lane 0.  Chunks of 8*kWG partials are folded (8 per lane in registers, then
+// LDS) and combined with a binary-counter stack.
+__device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */, double *stack /* 16 */)
 {
-    constexpr int kPerLane = kMaxPartials / kWG;
+    constexpr uint32_t kPerLane = 8;
     uint32_t P2 = 1;
     while (P2 < P) P2 <<= 1;
-    const uint32_t C = P2 > (uint32_t)kWG ? P2 / kWG : 1;     // <= kPerLane
+    const uint32_t C = P2 > (uint32_t)kWG ? (P2 / kWG < kPerLane ? P2 / kWG : kPerLane) : 1;
+    const uint32_t chunk = C * kWG;
+    const uint32_t nchunks = P2 > chunk ? P2 / chunk : 1;
     const uint32_t tid = threadIdx.x;
-    double v[kPerLane];
+    double result = 0.0;
+    for (uint32_t ch = 0; ch < nchunks; ++ch) {
+        double v[kPerLane];
 #pragma unroll
-    for (uint32_t k = 0; k < (uint32_t)kPerLane; ++k) {
-        uint32_t idx = tid * C + k;
-        v[k] = (k < C && idx < P)
-                   ? __hip_atomic_load(part + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                   : 0.0;
-    }
+        for (uint32_t k = 0; k < kPerLane; ++k) {
+            const uint32_t idx = ch * chunk + tid * C + k;
+            v[k] = (k < C && idx < P)
+                       ? __hip_atomic_load(part + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                       : 0.0;
+        }
 #pragma unroll
-    for (int s = 1; s < kPerLane; s <<= 1)
+        for (uint32_t s = 1; s < kPerLane; s <<= 1)
 #pragma unroll
-        for (int k = 0; k < kPerLane; k += 2 * s) v[k] = v[k] + v[k + s];
-    __syncthreads();
-    lds[tid] = v[0];
-    __syncthreads();
-    for (uint32_t n = kWG; n > 1; n >>= 1) {
-        double t = 0.0;
-        if (tid < n / 2) t = lds[2 * tid] + lds[2 * tid + 1];
+            for (uint32_t k = 0; k < kPerLane; k += 2 * s) v[k] = v[k] + v[k + s];
         __syncthreads();
-        if (tid < n / 2) lds[tid] = t;
+        lds[tid] = v[0];
         __syncthreads();
+        for (uint32_t n = kWG; n > 1; n >>= 1) {
+            double t = 0.0;
+            if (tid < n / 2) t = lds[2 * tid] + lds[2 * tid + 1];
+            __syncthreads();
+            if (tid < n / 2) lds[tid] = t;
+            __syncthreads();
+        }
+        if (tid == 0) {
+            double x = lds[0];
+            uint32_t lvl = 0;
+            while ((ch >> lvl) & 1u) { x = stack[lvl] + x; ++lvl; }
+            stack[lvl] = x;
+            result = x;
+        }
     }
-    return lds[0];
+    return result;
+}
+
+// which tensor of the launch this workgroup works on, and its index there
+__device__ __forceinline__ uint32_t find_task(const Batch &b, uint32_t &lwg)
+{
+    uint32_t k = 0;
+    for (uint32_t j = 1; j < b.n; ++j)
+        if (blockIdx.x >= b.t[j].wg_begin) k = j;
+    lwg = blockIdx.x - b.t[k].wg_begin;
+    return k;
 }
 
 // ------------------------------------------------------------------ kernels
+// clears the control words, arrival counters and partial maxima of every slot
+__global__ __launch_bounds__(kWG) void k_init(char *slots_base)
+{
+    uint32_t *p = reinterpret_cast<uint32_t *>(slots_base + (size_t)blockIdx.x * kSlotBytes);
+    for (uint32_t k = threadIdx.x; k < kZeroedBytes / 4; k += kWG) p[k] = 0u;
+}
+
 // max |w| over a tensor.  |bits| of finite floats order like the values; NaN
 // and Inf patterns are larger than every finite one, so they surface in the max.
-// One partial maximum per workgroup; workgroup 0 also resets the arrival
-// counters of the two kernels that follow on the stream.
 template <int DT>
 __device__ __forceinline__ uint32_t absmax16(uint4 v)
 {
@@ -318,40 +368,49 @@ __device__ __forceinline__ uint32_t absmax16(uint4 v)
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_absmax(const void *w, int64_t rows, int64_t row_chunks,
-                                                int64_t ld_chunks, Workspace ws)
+__global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
 {
     __shared__ uint32_t s_wave[4];
-    // a "chunk" is 16 bytes; a row holds row_chunks of them, rows are ld_chunks apart
-    const uint4 *base = static_cast<const uint4 *>(w);
+    __shared__ uint32_t s_last;
+    uint32_t lwg;
+    const Task &t = batch.t[find_task(batch, lwg)];
     const uint32_t tid = threadIdx.x;
-    if (blockIdx.x == 0 && blockIdx.y == 0) {
-        if (tid < kSlots) ws.slots_stats[tid * kSlotStride] = 0u;
-        else if (tid < 2 * kSlots) ws.slots_search[(tid - kSlots) * kSlotStride] = 0u;
-        if (tid == 0) {
-            ws.ctrl->top_stats = 0u;
-            ws.ctrl->top_search = 0u;
-            ws.ctrl->n_amax_parts = gridDim.x * gridDim.y;
-        }
-    }
+    constexpr int kChunks = DT == SOAR_BF16 ? 2 : 4;      // 16-byte pieces per block
+
     uint32_t m = 0;
-    const int64_t stride = (int64_t)gridDim.x * kWG;
-    for (int64_t r = blockIdx.y; r < rows; r += gridDim.y) {
-        const uint4 *p = base + r * ld_chunks;
-        int64_t c = (int64_t)blockIdx.x * kWG + tid;
-        for (; c + 3 * stride < row_chunks; c += 4 * stride) {
-            uint4 v0 = p[c], v1 = p[c + stride], v2 = p[c + 2 * stride], v3 = p[c + 3 * stride];
-            m = max(m, max(max(absmax16<DT>(v0), absmax16<DT>(v1)), max(absmax16<DT>(v2), absmax16<DT>(v3))));
-        }
-        for (; c < row_chunks; c += stride) m = max(m, absmax16<DT>(p[c]));
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        if (i >= t.nblk) break;
+        const size_t off = block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
+        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(t.w) + off);
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) m = max(m, absmax16<DT>(p[c]));
     }
     if constexpr (DT == SOAR_BF16) m <<= 16;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) m = max(m, (uint32_t)__shfl_xor((int)m, s, 64));
+    m = wave_max_u32(m);
     if ((tid & 63) == 0) s_wave[tid >> 6] = m;
     __syncthreads();
-    if (tid == 0)
-        ws.amax_part[blockIdx.y * gridDim.x + blockIdx.x] = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
+    uint32_t *counters = t.counters;                       // kernel 0
+    if (tid == 0) {
+        m = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
+        const uint32_t ns = t.n_wg < (uint32_t)kSlots ? t.n_wg : (uint32_t)kSlots;
+        // arrive_is_last waits for this read-modify-write to complete before it counts the workgroup in
+        __hip_atomic_fetch_max(t.slot_max + (lwg % ns) * kSlotStride, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = arrive_is_last(counters, &t.ctrl->top[0], t.n_wg, lwg) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    if (tid < 64) {
+        uint32_t v = tid < kSlots ? __hip_atomic_load(t.slot_max + tid * kSlotStride, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_AGENT)
+                                  : 0u;
+        v = wave_max_u32(v);
+        if (tid == 0) t.ctrl->amax_bits = v;
+    }
+    __syncthreads();
+    if (tid < kSlots) t.slot_max[tid * kSlotStride] = 0u;
+    reset_counters(counters, &t.ctrl->top[0]);
 }
 
 // Eq. 1-2 per block and the two tensor-wide sums of Eq. 5.  The per-block terms
@@ -360,45 +419,45 @@ __global__ __launch_bounds__(kWG) void k_absmax(const void *w, int64_t rows, int
 // which is the same adjacent-pair tree at a fraction of the cross-lane work.
 // Each block's (a, b) -- or (Delta0, 0) when its codes are all zero -- is kept
 // for the search kernel.
-constexpr int kStage = 4;
-
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_global_scale)
+__global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
 {
     __shared__ double2 s_terms[kStage * kWG];
     __shared__ double s_wave[2][4];
     __shared__ double s_stack[2][32];
     __shared__ double s_tree[kWG];
-    __shared__ uint32_t s_u32[4];
     __shared__ uint32_t s_last;
 
+    uint32_t lwg;
+    const Task &t = batch.t[find_task(batch, lwg)];
     const uint32_t tid = threadIdx.x;
-    const uint32_t amax_bits = reduce_amax(ws.amax_part, ws.ctrl->n_amax_parts, s_u32);
+    const uint32_t amax_bits = t.ctrl->amax_bits;
     const bool degenerate = amax_bits == 0u || amax_bits >= 0x7F800000u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
 
     double wgN = 0.0, wgM = 0.0;
-    const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
-    const uint32_t T = g.tiles_per_wg < (uint32_t)kStage ? g.tiles_per_wg : (uint32_t)kStage;   // power of two
-    for (uint32_t kg = 0; kg < g.tiles_per_wg; kg += T) {
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    const uint32_t T = t.tiles_per_wg < (uint32_t)kStage ? t.tiles_per_wg : (uint32_t)kStage;   // power of two
+    for (uint32_t kg = 0; kg < t.tiles_per_wg; kg += T) {
         for (uint32_t kk = 0; kk < T; ++kk) {
             const uint32_t i = (tile0 + kg + kk) * kWG + tid;
             double tN = 0.0, tM = 0.0;
-            if (i < g.nblk) {
+            if (i < t.nblk) {
                 float a = 0.0f, b = 0.0f;
                 if (!degenerate) {
                     float w[16], q[16];
                     uint32_t nib[2], c0;
                     float delta0;
-                    load_block<DT>(g.w, block_offset(g, i), w);
+                    load_block<DT>(t.w, block_offset(t, i), w);
                     block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
                     block_sums(w, q, a, b);
                     tN = (double)a * (double)delta0;
                     tM = ((double)b * (double)delta0) * (double)delta0;
                     if (b == 0.0f) a = delta0;
                 }
-                ws.ab[i] = make_float2(a, b);
+                t.a[i] = a;
+                t.b4[i] = (uint16_t)(b * 4.0f);        // exact: b is a multiple of 1/4, at most 576
             }
             s_terms[kk * kWG + tid] = make_double2(tN, tM);
         }
@@ -436,26 +495,28 @@ __global__ __launch_bounds__(kWG) void k_stats(Geom g, Workspace ws, float *d_gl
             wgN = vN; wgM = vM;          // after the last group: the sum of all tiles
         }
     }
+    double *partN = t.part, *partM = t.part + kMaxPartials;
+    uint32_t *counters = t.counters + 1 * kSlots * kSlotStride;
     if (tid == 0) {
-        publish(ws.partN + blockIdx.x, wgN);
-        publish(ws.partM + blockIdx.x, wgM);
-        s_last = arrive_is_last(ws.slots_stats, &ws.ctrl->top_stats) ? 1u : 0u;
+        publish(partN + lwg, wgN);
+        publish(partM + lwg, wgM);
+        s_last = arrive_is_last(counters, &t.ctrl->top[1], t.n_wg, lwg) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
-    // last workgroup to arrive: finish the trees and apply Eq. 5
-    double N = tree_of_partials(ws.partN, gridDim.x, s_tree);
-    double M = tree_of_partials(ws.partM, gridDim.x, s_tree);
+    // last workgroup of the tensor: finish the trees and apply Eq. 5
+    const double N = tree_of_partials(partN, t.n_wg, s_tree, s_stack[0]);
+    const double M = tree_of_partials(partM, t.n_wg, s_tree, s_stack[1]);
     if (tid == 0) {
         float alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;
         if (amax_bits == 0u) alpha1 = 1.0f;
-        ws.ctrl->amax_bits = amax_bits;
-        ws.ctrl->alpha0 = alpha0;
-        ws.ctrl->alpha1 = alpha1;
-        ws.ctrl->N = N;
-        ws.ctrl->M = M;
-        *d_global_scale = alpha1;
+        t.ctrl->alpha0 = alpha0;
+        t.ctrl->alpha1 = alpha1;
+        t.ctrl->N = N;
+        t.ctrl->M = M;
+        *t.gscale = alpha1;
     }
+    reset_counters(counters, &t.ctrl->top[1]);
 }
 
 // Exhaustive form of the Eq. 8 search: candidates centre, -1, +1, -2, +2, ...;
@@ -530,35 +591,33 @@ __device__ __forceinline__ bool search_certified(const float w[16], const float 
 // Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
 // METHOD RTN emits the Eq. 1-2 state instead.
 template <int DT, int METHOD>
-__global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius, int full_search,
-                                                uint8_t *codes, uint8_t *scales, float *d_global_scale,
-                                                double *d_sse, int32_t *d_status)
+__global__ __launch_bounds__(kWG) void k_search(const Batch batch)
 {
     __shared__ double s_wave[4];
     __shared__ double s_tree[kWG];
-    __shared__ uint32_t s_u32[4];
+    __shared__ double s_stack[16];
     __shared__ uint32_t s_last;
 
+    uint32_t lwg;
+    const Task &t = batch.t[find_task(batch, lwg)];
     const uint32_t tid = threadIdx.x;
-    uint32_t amax_bits;
-    if constexpr (METHOD == SOAR_METHOD_SOAR)
-        amax_bits = ws.ctrl->amax_bits;                 // left by the stats kernel
-    else
-        amax_bits = reduce_amax(ws.amax_part, ws.ctrl->n_amax_parts, s_u32);
+    const int radius = batch.radius;
+    const bool full_search = batch.full_search != 0;
+    const uint32_t amax_bits = t.ctrl->amax_bits;
     const bool allzero = amax_bits == 0u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
-    const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? ws.ctrl->alpha1 : alpha0;
+    const float alpha1 = (METHOD == SOAR_METHOD_SOAR) ? t.ctrl->alpha1 : alpha0;
     const float inv_alpha1 = __builtin_amdgcn_rcpf(alpha1);
 
     double sse = 0.0;
-    const uint32_t tile0 = blockIdx.x * g.tiles_per_wg;
-    for (uint32_t k = 0; k < g.tiles_per_wg; ++k) {
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
         const uint32_t i = (tile0 + k) * kWG + tid;
-        if (i >= g.nblk) continue;
+        if (i >= t.nblk) break;
         float w[16], q[16];
         uint32_t nib[2];
-        load_block<DT>(g.w, block_offset(g, i), w);
+        load_block<DT>(t.w, block_offset(t, i), w);
         uint32_t out_code;
         float out_err;
         if (allzero) {
@@ -577,8 +636,9 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius
             out_code = c0;
             out_err = block_error(w, q, alpha0 * delta0);
         } else {
-            const float2 ab = ws.ab[i];       // (a, b), or (Delta0, 0)
-            const float delta_star = (ab.y == 0.0f) ? ab.x : ab.x / (alpha1 * ab.y);
+            const float a = t.a[i];                    // a, or Delta0 where b == 0
+            const float b = (float)t.b4[i] * 0.25f;
+            const float delta_star = (b == 0.0f) ? a : a / (alpha1 * b);
             const int centre = (int)e4m3_project(delta_star);
             assign_codes(w, alpha1 * delta_star, nib, q);
             int best;
@@ -589,33 +649,36 @@ __global__ __launch_bounds__(kWG) void k_search(Geom g, Workspace ws, int radius
             out_code = (uint32_t)best;
             out_err = best_err;
         }
-        reinterpret_cast<uint2 *>(codes)[i] = make_uint2(nib[0], nib[1]);
-        scales[i] = (uint8_t)out_code;
+        reinterpret_cast<uint2 *>(t.codes)[i] = make_uint2(nib[0], nib[1]);
+        t.scales[i] = (uint8_t)out_code;
         sse += (double)out_err;
     }
     // error sum: fixed order for a given launch shape
     sse = wave_pair_tree(sse);
     if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
     __syncthreads();
+    double *partS = t.part + 2 * kMaxPartials;
+    uint32_t *counters = t.counters + 2 * kSlots * kSlotStride;
     if (tid == 0) {
-        publish(ws.partS + blockIdx.x, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
-        s_last = arrive_is_last(ws.slots_search, &ws.ctrl->top_search) ? 1u : 0u;
+        publish(partS + lwg, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
+        s_last = arrive_is_last(counters, &t.ctrl->top[2], t.n_wg, lwg) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
-    double total = tree_of_partials(ws.partS, gridDim.x, s_tree);
+    const double total = tree_of_partials(partS, t.n_wg, s_tree, s_stack);
     if (tid == 0) {
-        if (d_sse) *d_sse = total;
-        if (d_status)
-            *d_status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
-        if (METHOD == SOAR_METHOD_RTN) *d_global_scale = allzero ? 1.0f : alpha0;
+        if (t.sse) *t.sse = total;
+        if (t.status)
+            *t.status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
+        if (METHOD == SOAR_METHOD_RTN) *t.gscale = allzero ? 1.0f : alpha0;
     }
+    reset_counters(counters, &t.ctrl->top[2]);
 }
 
 // Eq. 3
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
-                                                 const float *d_global_scale, Geom g, void *out)
+                                                 const float *d_global_scale, Task g, void *out)
 {
     const uint32_t i = blockIdx.x * kWG + threadIdx.x;
     if (i >= g.nblk) return;
@@ -652,7 +715,7 @@ __global__ void k_zero_f64(double *p) { *p = 0.0; }
 
 // Eq. 4 for stored codes and scales
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_recon(Geom g, const uint8_t *codes, const uint8_t *scales,
+__global__ __launch_bounds__(kWG) void k_recon(Task g, const uint8_t *codes, const uint8_t *scales,
                                                const float *d_global_scale, double *d_sse)
 {
     __shared__ double s_wave[4];
@@ -689,7 +752,6 @@ __global__ void k_e4m3_project(const float *x, int64_t n, uint8_t *out)
 struct Timing {
     bool enabled = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[SOAR_KERNEL_COUNT];
-    std::vector<hipEvent_t> pool;
 };
 Timing g_timing;
 
@@ -726,9 +788,9 @@ bool valid_params(const soar_params *p)
 soar_status check_shape(int64_t rows, int64_t cols, int64_t ld)
 {
     if (rows <= 0 || cols <= 0 || cols % 16 != 0 || ld < cols) return SOAR_ERR_SHAPE;
-    // block count must fit the kernels' 32-bit block index with a tile of slack
+    // block count must fit the kernels' 32-bit block index with a few tiles of slack
     if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31) return SOAR_ERR_SHAPE;
-    if (rows * (cols / 16) > ((int64_t)1 << 31) - 2 * kWG) return SOAR_ERR_SHAPE;
+    if (rows * (cols / 16) > ((int64_t)1 << 31) - 16 * kWG) return SOAR_ERR_SHAPE;
     return SOAR_OK;
 }
 
@@ -740,21 +802,33 @@ soar_status check_matrix_ptr(const void *p, int dtype, int64_t ld)
     return SOAR_OK;
 }
 
-Geom make_geom(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t *n_wg, uint32_t forced_tpw = 0)
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+// bytes of per-block workspace (a: float, b4: uint16) of one tensor
+size_t per_block_bytes(int64_t rows, int64_t cols)
 {
-    Geom g;
-    g.w = w;
-    g.ld = ld;
-    g.bpr = (uint32_t)(cols / 16);
-    g.nblk = (uint32_t)(rows * (cols / 16));
-    g.contiguous = (ld == cols) ? 1u : 0u;
-    const uint32_t tiles = (g.nblk + kWG - 1) / kWG;
+    const size_t nblk = (size_t)(rows * (cols / 16));
+    return align256(nblk * sizeof(float)) + align256(nblk * sizeof(uint16_t));
+}
+
+// addressing and launch shape of one tensor; the workspace fields stay unset
+Task make_task(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t forced_tpw)
+{
+    Task t;
+    std::memset(&t, 0, sizeof(t));
+    t.w = w;
+    t.ld = ld;
+    t.bpr = (uint32_t)(cols / 16);
+    t.nblk = (uint32_t)(rows * (cols / 16));
+    t.contiguous = (ld == cols) ? 1u : 0u;
+    const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
     uint32_t tpw = 1;
+    while (tpw < (uint32_t)kStage && tpw * 2 <= tiles) tpw <<= 1;
     if (forced_tpw) tpw = forced_tpw;
     while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
-    g.tiles_per_wg = tpw;
-    *n_wg = (tiles + tpw - 1) / tpw;
-    return g;
+    t.tiles_per_wg = tpw;
+    t.n_wg = (tiles + tpw - 1) / tpw;
+    return t;
 }
 
 #define SOAR_LAUNCH_CHECK()                                  \
@@ -762,78 +836,125 @@ Geom make_geom(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t *
         if (hipGetLastError() != hipSuccess) return SOAR_ERR_HIP; \
     } while (0)
 
-soar_status validate_quantize(const void *d_w, int dtype, int64_t rows, int64_t cols, int64_t ld,
-                              const soar_params *params, const uint8_t *d_codes, const uint8_t *d_scales,
-                              const float *d_global_scale, const void *d_workspace, size_t workspace_bytes)
+soar_status validate_tensor(const soar_tensor_desc &d, const soar_params *params)
 {
-    if (!d_w || !d_codes || !d_scales || !d_global_scale || !params) return SOAR_ERR_NULL;
-    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    if (!d.d_w || !d.d_codes || !d.d_scales || !d.d_global_scale) return SOAR_ERR_NULL;
+    if (d.dtype != SOAR_BF16 && d.dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
     if (!valid_params(params)) return SOAR_ERR_PARAM;
-    soar_status s = check_shape(rows, cols, ld);
+    soar_status s = check_shape(d.rows, d.cols, d.ld_elems);
     if (s != SOAR_OK) return s;
-    s = check_matrix_ptr(d_w, dtype, ld);
+    s = check_matrix_ptr(d.d_w, d.dtype, d.ld_elems);
     if (s != SOAR_OK) return s;
-    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
-    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
-    if (workspace_bytes < soar_workspace_bytes(rows, cols, params)) return SOAR_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(d.d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
     return SOAR_OK;
 }
 
-Workspace carve(void *d_workspace)
+// how many tensors starting at `first` go into one launch
+int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
 {
-    char *p = static_cast<char *>(d_workspace);
-    Workspace ws;
-    ws.ctrl = reinterpret_cast<Ctrl *>(p);                 p += kCtrlBytes;
-    ws.slots_stats = reinterpret_cast<uint32_t *>(p);      p += kSlots * kSlotStride * 4;
-    ws.slots_search = reinterpret_cast<uint32_t *>(p);     p += kSlots * kSlotStride * 4;
-    ws.amax_part = reinterpret_cast<uint32_t *>(p);        p += kMaxAmaxParts * 4;
-    ws.partN = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
-    ws.partM = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
-    ws.partS = reinterpret_cast<double *>(p);              p += sizeof(double) * kMaxPartials;
-    ws.ab = reinterpret_cast<float2 *>(p);
-    return ws;
+    int64_t elems = descs[first].rows * descs[first].cols;
+    int32_t j = first + 1;
+    while (j < n && j - first < kGroupMax && descs[j].dtype == descs[first].dtype &&
+           elems + descs[j].rows * descs[j].cols <= kGroupElemCap) {
+        elems += descs[j].rows * descs[j].cols;
+        ++j;
+    }
+    return j;
+}
+
+size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs)
+{
+    size_t most = 0;
+    for (int32_t i = 0; i < n;) {
+        const int32_t j = group_end(n, descs, i);
+        size_t sum = 0;
+        for (int32_t k = i; k < j; ++k) sum += per_block_bytes(descs[k].rows, descs[k].cols);
+        if (sum > most) most = sum;
+        i = j;
+    }
+    return (size_t)kGroupMax * kSlotBytes + most;
 }
 
 template <int DT>
-soar_status enqueue_quantize(const void *d_w, int64_t rows, int64_t cols, int64_t ld, const soar_params *params,
-                             uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale, double *d_sse,
-                             int32_t *d_status, void *d_workspace, hipStream_t st)
+soar_status launch_group(const Batch &b, uint32_t total_wg, int method, hipStream_t st)
 {
-    const Workspace ws = carve(d_workspace);
-    uint32_t n_wg = 0;
-    const Geom g = make_geom(d_w, rows, cols, ld, &n_wg, (uint32_t)params->tiles_per_wg);
-    const int64_t es = DT == SOAR_BF16 ? 2 : 4;
     {
         ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
-        int64_t a_rows = rows, row_chunks = cols * es / 16, ld_chunks = ld * es / 16;
-        if (ld == cols) { row_chunks *= rows; a_rows = 1; ld_chunks = row_chunks; }
-        // about 8 chunks per lane, at most kMaxAmaxParts workgroups in all
-        int64_t gx = (row_chunks + (int64_t)kWG * 8 - 1) / ((int64_t)kWG * 8);
-        if (gx > kMaxAmaxParts) gx = kMaxAmaxParts;
-        if (gx < 1) gx = 1;
-        int64_t gy = a_rows;
-        const int64_t gy_cap = kMaxAmaxParts / gx;
-        if (gy > gy_cap) gy = gy_cap;
-        hipLaunchKernelGGL(k_absmax<DT>, dim3((uint32_t)gx, (uint32_t)gy), dim3(kWG), 0, st, d_w, a_rows,
-                           row_chunks, ld_chunks, ws);
+        hipLaunchKernelGGL(k_absmax<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     }
-    if (params->method == SOAR_METHOD_SOAR) {
+    if (method == SOAR_METHOD_SOAR) {
         {
             ScopedTimer t(SOAR_KERNEL_STATS, st);
-            hipLaunchKernelGGL(k_stats<DT>, dim3(n_wg), dim3(kWG), 0, st, g, ws, d_global_scale);
+            hipLaunchKernelGGL(k_stats<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
             SOAR_LAUNCH_CHECK();
         }
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(n_wg), dim3(kWG), 0, st, g, ws,
-                           params->dss_radius, params->search_mode == SOAR_SEARCH_FULL ? 1 : 0, d_codes,
-                           d_scales, d_global_scale, d_sse, d_status);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(total_wg), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     } else {
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(n_wg), dim3(kWG), 0, st, g, ws, 0, 1, d_codes,
-                           d_scales, d_global_scale, d_sse, d_status);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(total_wg), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
+    }
+    return SOAR_OK;
+}
+
+soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params, void *d_workspace,
+                      size_t workspace_bytes, hipStream_t st)
+{
+    if (n < 0) return SOAR_ERR_SHAPE;
+    if (n > 0 && !descs) return SOAR_ERR_NULL;
+    if (!params) return SOAR_ERR_NULL;
+    if (!valid_params(params)) return SOAR_ERR_PARAM;
+    for (int32_t k = 0; k < n; ++k) {
+        soar_status s = validate_tensor(descs[k], params);
+        if (s != SOAR_OK) return s;
+    }
+    if (n == 0) return SOAR_OK;
+    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
+    if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
+
+    char *base = static_cast<char *>(d_workspace);
+    {
+        ScopedTimer t(SOAR_KERNEL_INIT, st);
+        hipLaunchKernelGGL(k_init, dim3(kGroupMax), dim3(kWG), 0, st, base);
+        SOAR_LAUNCH_CHECK();
+    }
+    for (int32_t i = 0; i < n;) {
+        const int32_t j = group_end(n, descs, i);
+        Batch b;
+        std::memset(&b, 0, sizeof(b));
+        b.n = (uint32_t)(j - i);
+        b.radius = params->dss_radius;
+        b.full_search = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        uint32_t wg = 0;
+        char *per_block = base + (size_t)kGroupMax * kSlotBytes;
+        for (int32_t k = i; k < j; ++k) {
+            const soar_tensor_desc &d = descs[k];
+            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, (uint32_t)params->tiles_per_wg);
+            t.codes = d.d_codes;
+            t.scales = d.d_scales;
+            t.gscale = d.d_global_scale;
+            t.sse = d.d_sse;
+            t.status = d.d_status;
+            t.wg_begin = wg;
+            wg += t.n_wg;
+            char *slot = base + (size_t)(k - i) * kSlotBytes;
+            t.ctrl = reinterpret_cast<Ctrl *>(slot);
+            t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
+            t.slot_max = reinterpret_cast<uint32_t *>(slot + kCtrlBytes + kCountersBytes);
+            t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
+            t.a = reinterpret_cast<float *>(per_block);
+            per_block += align256((size_t)t.nblk * sizeof(float));
+            t.b4 = reinterpret_cast<uint16_t *>(per_block);
+            per_block += align256((size_t)t.nblk * sizeof(uint16_t));
+            b.t[k - i] = t;
+        }
+        soar_status s = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, st)
+                                                    : launch_group<SOAR_FP32>(b, wg, params->method, st);
+        if (s != SOAR_OK) return s;
+        i = j;
     }
     return SOAR_OK;
 }
@@ -857,13 +978,21 @@ void soar_default_params(soar_params *p)
     p->beta_hi = 1.0f;
     p->early_stop_rel = 1e-3f;
     p->search_mode = SOAR_SEARCH_AUTO;
+    p->tiles_per_wg = 0;
 }
 
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)
 {
     if (!valid_params(params) || check_shape(rows, cols, cols) != SOAR_OK) return 0;
-    const size_t per_block = sizeof(float2) * (size_t)(rows * (cols / 16));
-    return kFixedWorkspaceBytes + ((per_block + 255) / 256) * 256;
+    return (size_t)kGroupMax * kSlotBytes + per_block_bytes(rows, cols);
+}
+
+size_t soar_batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs, const soar_params *params)
+{
+    if (n <= 0 || !descs || !valid_params(params)) return 0;
+    for (int32_t k = 0; k < n; ++k)
+        if (check_shape(descs[k].rows, descs[k].cols, descs[k].ld_elems) != SOAR_OK) return 0;
+    return batch_workspace_bytes(n, descs);
 }
 
 soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
@@ -871,36 +1000,24 @@ soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64
                           float *d_global_scale, double *d_sse, int32_t *d_status, void *d_workspace,
                           size_t workspace_bytes, void *hip_stream)
 {
-    soar_status s = validate_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales,
-                                      d_global_scale, d_workspace, workspace_bytes);
-    if (s != SOAR_OK) return s;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (dtype == SOAR_BF16)
-        return enqueue_quantize<SOAR_BF16>(d_w, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
-                                           d_sse, d_status, d_workspace, st);
-    return enqueue_quantize<SOAR_FP32>(d_w, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
-                                       d_sse, d_status, d_workspace, st);
+    soar_tensor_desc d;
+    d.d_w = d_w;
+    d.dtype = dtype;
+    d.rows = rows;
+    d.cols = cols;
+    d.ld_elems = ld_elems;
+    d.d_codes = d_codes;
+    d.d_scales = d_scales;
+    d.d_global_scale = d_global_scale;
+    d.d_sse = d_sse;
+    d.d_status = d_status;
+    return run_batch(1, &d, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params,
                                 void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (n < 0) return SOAR_ERR_SHAPE;
-    if (n > 0 && !descs) return SOAR_ERR_NULL;
-    for (int32_t k = 0; k < n; ++k) {
-        const soar_tensor_desc &d = descs[k];
-        soar_status s = validate_quantize(d.d_w, d.dtype, d.rows, d.cols, d.ld_elems, params, d.d_codes,
-                                          d.d_scales, d.d_global_scale, d_workspace, workspace_bytes);
-        if (s != SOAR_OK) return s;
-    }
-    for (int32_t k = 0; k < n; ++k) {
-        const soar_tensor_desc &d = descs[k];
-        soar_status s = soar_quantize(d.d_w, (soar_dtype)d.dtype, d.rows, d.cols, d.ld_elems, params, d.d_codes,
-                                      d.d_scales, d.d_global_scale, d.d_sse, d.d_status, d_workspace,
-                                      workspace_bytes, hip_stream);
-        if (s != SOAR_OK) return s;
-    }
-    return SOAR_OK;
+    return run_batch(n, descs, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 soar_status soar_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, const float *d_global_scale,
@@ -915,8 +1032,7 @@ soar_status soar_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, con
     if (s != SOAR_OK) return s;
     if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    uint32_t n_wg = 0;
-    Geom g = make_geom(d_out, rows, cols, ld_elems, &n_wg);
+    Task g = make_task(d_out, rows, cols, ld_elems, 0);
     const uint32_t grid = (g.nblk + kWG - 1) / kWG;
     ScopedTimer t(SOAR_KERNEL_DEQUANT, st);
     if (out_dtype == SOAR_BF16)
@@ -939,8 +1055,7 @@ soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, in
     if (s != SOAR_OK) return s;
     if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    uint32_t n_wg = 0;
-    Geom g = make_geom(d_w, rows, cols, ld_elems, &n_wg);
+    Task g = make_task(d_w, rows, cols, ld_elems, 0);
     uint32_t grid = (g.nblk + kWG - 1) / kWG;
     if (grid > 2048) grid = 2048;
     ScopedTimer t(SOAR_KERNEL_RECON, st);

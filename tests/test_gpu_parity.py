@@ -109,7 +109,6 @@ def test_single_tensor_workloads_full_size(workload, method):
 def test_multi_tensor_workloads_scaled_down_batch(workload, div):
     specs = synth.workload_specs(workload, div)[:21]
     p = B.soar_default_params(B.SOAR_METHOD_SOAR, specs[0].dss_radius)
-    ws = B.new_workspace(max(s.rows for s in specs), max(s.cols for s in specs), p, DEV)
     ws_list, outs, descs = [], [], []
     for s in specs:
         w = synth.make_weight(s, DEV)
@@ -119,6 +118,7 @@ def test_multi_tensor_workloads_scaled_down_batch(workload, div):
                         torch.empty(1, dtype=torch.float64, device=DEV),
                         torch.empty(1, dtype=torch.int32, device=DEV))
         ws_list.append(w); outs.append(o); descs.append(B.make_desc(w, o))
+    ws = B.new_batch_workspace(descs, p, DEV)
     B.quantize_batch(descs, p, ws)
     torch.cuda.synchronize()
     for s, w, o in zip(specs, ws_list, outs):
