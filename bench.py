@@ -35,6 +35,7 @@ def parse_args():
     ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--layers", type=int, default=0, help="workloads 4/5: first N layers only (0 = all)")
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
+    ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -78,7 +79,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
-    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode)
+    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw)
     descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
     ws = B.new_batch_workspace(descs, params, dev)
 
