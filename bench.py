@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="workloads 4/5: first N layers only (0 = all)")
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
+    ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -79,7 +80,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
-    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw)
+    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
     descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
     ws = B.new_batch_workspace(descs, params, dev)
 
@@ -105,14 +106,16 @@ def main():
     sse_soar = sum(float(o.sse.item()) for o in outs)
     statuses = [int(o.status.item()) for o in outs]
 
-    # ---- per-kernel durations (HIP events on the launch stream), same steps again
+    # ---- per-kernel durations: HIP events around every launch, on the stream it is
+    # launched on; same steps again, on one stream so that a kernel's duration is its own
     roofline = None
     kernels = {}
     if not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
+        p_one = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, streams=1)
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
-            step()
+            B.quantize_batch(descs, p_one, ws)
         torch.cuda.synchronize()
         names = {B.SOAR_KERNEL_INIT: "init", B.SOAR_KERNEL_ABSMAX: "absmax",
                  B.SOAR_KERNEL_STATS: "stats", B.SOAR_KERNEL_SEARCH: "search"}

@@ -78,6 +78,10 @@ typedef struct {
     int32_t  tiles_per_wg;   /* 0 = chosen by the library; a power of two <= 65536
                                 forces how many 256-block tiles one workgroup walks
                                 (for tests: outputs must not depend on it)          */
+    int32_t  streams;        /* soar_quantize_batch: 0 = library default (launch
+                                groups alternate between the caller's stream and one
+                                internal stream, forked and joined by events);
+                                1 = everything on the caller's stream             */
 } soar_params;
 
 /* Fills *p with the hot-path defaults: SOAR, block 16, T = 1, K = 4, beta = {1}. */

@@ -46,7 +46,7 @@ class soar_params(C.Structure):
         ("struct_size", C.c_uint32), ("method", C.c_int32), ("block", C.c_int32),
         ("iters", C.c_int32), ("dss_radius", C.c_int32), ("n_beta", C.c_int32),
         ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
-        ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32),
+        ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32), ("streams", C.c_int32),
     ]
 
 
@@ -104,13 +104,15 @@ def lib():
 
 # ------------------------------------------------------------------ raw entry points
 def soar_default_params(method: int = SOAR_METHOD_SOAR, dss_radius: int = 4,
-                        search_mode: int = SOAR_SEARCH_AUTO, tiles_per_wg: int = 0) -> soar_params:
+                        search_mode: int = SOAR_SEARCH_AUTO, tiles_per_wg: int = 0,
+                        streams: int = 0) -> soar_params:
     p = soar_params()
     lib().soar_default_params(C.byref(p))
     p.method = method
     p.dss_radius = dss_radius
     p.search_mode = search_mode
     p.tiles_per_wg = tiles_per_wg
+    p.streams = streams
     return p
 
 

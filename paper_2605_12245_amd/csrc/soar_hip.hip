@@ -27,7 +27,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
-#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -43,6 +42,7 @@ constexpr int64_t kGroupElemCap = (int64_t)1 << 28;   // weights per launch (bey
 constexpr int kSlots = 64;               // first-level arrival counters
 constexpr int kSlotStride = 32;          // in uint32: one counter per 128 bytes
 constexpr int kKernels = 3;              // absmax, stats, search
+constexpr int kLanes = 2;                // streams a batch is spread over
 constexpr uint32_t kE4M3Min = 0x01u, kE4M3Max = 0x7Eu;
 
 // Control words of one tensor slot.  soar_quantize* zeroes them once per call;
@@ -92,7 +92,6 @@ struct Batch {
     uint32_t n;
     int32_t  radius;
     int32_t  full_search;
-    int32_t  debug;
 };
 
 typedef Task Geom;           // the addressing fields are all block_offset needs
@@ -399,7 +398,6 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
 #pragma unroll
         for (int c = 0; c < kChunks; ++c) m = max(m, absmax16<DT>(p[c]));
     }
-    if (batch.debug & 1) { if (m == 0x12345678u) t.ctrl->pad = m; return; }
     if constexpr (DT == SOAR_BF16) m <<= 16;
     m = wave_max_u32(m);
     if ((tid & 63) == 0) s_wave[tid >> 6] = m;
@@ -795,6 +793,7 @@ bool valid_params(const soar_params *p)
     if (p->dss_radius < 0 || p->dss_radius > 125) return false;
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    if (p->streams < 0 || p->streams > kLanes) return false;
     return true;
 }
 
@@ -875,17 +874,49 @@ int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
     return j;
 }
 
-size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs)
+// most per-block workspace any one launch of the batch needs
+size_t max_group_per_block_bytes(int32_t n, const soar_tensor_desc *descs, int32_t *n_groups)
 {
     size_t most = 0;
+    int32_t groups = 0;
     for (int32_t i = 0; i < n;) {
         const int32_t j = group_end(n, descs, i);
         size_t sum = 0;
         for (int32_t k = i; k < j; ++k) sum += per_block_bytes(descs[k].rows, descs[k].cols);
         if (sum > most) most = sum;
         i = j;
+        ++groups;
     }
-    return (size_t)kGroupMax * kSlotBytes + most;
+    if (n_groups) *n_groups = groups;
+    return most;
+}
+
+// A batch of two or more launch groups is spread over two streams (the caller's
+// and one of the library's own, forked and joined with events), so that the
+// memory-only and the arithmetic-heavy kernels of different groups overlap.
+// Each stream works in its own half of the workspace.
+
+size_t lane_workspace_bytes(size_t group_per_block) { return (size_t)kGroupMax * kSlotBytes + group_per_block; }
+
+size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs)
+{
+    int32_t groups = 0;
+    const size_t most = max_group_per_block_bytes(n, descs, &groups);
+    return (groups > 1 ? kLanes : 1) * lane_workspace_bytes(most);
+}
+
+hipStream_t aux_stream()
+{
+    // one per device, created on first use, default priority, never destroyed
+    static hipStream_t streams[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    if (!streams[dev]) {
+        hipStream_t st = nullptr;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        streams[dev] = st;
+    }
+    return streams[dev];
 }
 
 template <int DT>
@@ -928,22 +959,46 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
     if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
 
+    int32_t n_groups = 0;
+    const size_t lane_bytes = lane_workspace_bytes(max_group_per_block_bytes(n, descs, &n_groups));
+    const int lanes = (n_groups > 1 && params->streams != 1) ? kLanes : 1;
     char *base = static_cast<char *>(d_workspace);
+
+    hipStream_t lane_stream[kLanes] = {st, st};
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    if (lanes > 1) {
+        lane_stream[1] = aux_stream();
+        if (!lane_stream[1]) return SOAR_ERR_HIP;
+        if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return SOAR_ERR_HIP;
+        if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
+            (void)hipEventDestroy(ev_fork);
+            return SOAR_ERR_HIP;
+        }
+    }
+    soar_status result = SOAR_OK;
     {
         ScopedTimer t(SOAR_KERNEL_INIT, st);
-        hipLaunchKernelGGL(k_init, dim3(kGroupMax), dim3(kWG), 0, st, base);
-        SOAR_LAUNCH_CHECK();
+        for (int l = 0; l < lanes && result == SOAR_OK; ++l) {
+            hipLaunchKernelGGL(k_init, dim3(kGroupMax), dim3(kWG), 0, st, base + (size_t)l * lane_bytes);
+            if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
+        }
     }
-    for (int32_t i = 0; i < n;) {
+    if (lanes > 1 && result == SOAR_OK) {
+        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(lane_stream[1], ev_fork, 0) != hipSuccess)
+            result = SOAR_ERR_HIP;
+    }
+    int32_t g = 0;
+    for (int32_t i = 0; i < n && result == SOAR_OK; ++g) {
         const int32_t j = group_end(n, descs, i);
+        const int lane = g % lanes;
+        char *lane_base = base + (size_t)lane * lane_bytes;
         Batch b;
         std::memset(&b, 0, sizeof(b));
         b.n = (uint32_t)(j - i);
         b.radius = params->dss_radius;
         b.full_search = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
-        { const char *e = getenv("SOAR_DEBUG"); b.debug = e ? atoi(e) : 0; }
         uint32_t wg = 0;
-        char *per_block = base + (size_t)kGroupMax * kSlotBytes;
+        char *per_block = lane_base + (size_t)kGroupMax * kSlotBytes;
         for (int32_t k = i; k < j; ++k) {
             const soar_tensor_desc &d = descs[k];
             Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, (uint32_t)params->tiles_per_wg);
@@ -954,7 +1009,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             t.status = d.d_status;
             t.wg_begin = wg;
             wg += t.n_wg;
-            char *slot = base + (size_t)(k - i) * kSlotBytes;
+            char *slot = lane_base + (size_t)(k - i) * kSlotBytes;
             t.ctrl = reinterpret_cast<Ctrl *>(slot);
             t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
             t.slot_max = reinterpret_cast<uint32_t *>(slot + kCtrlBytes + kCountersBytes);
@@ -965,12 +1020,18 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             per_block += align256((size_t)t.nblk * sizeof(uint16_t));
             b.t[k - i] = t;
         }
-        soar_status s = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, st)
-                                                    : launch_group<SOAR_FP32>(b, wg, params->method, st);
-        if (s != SOAR_OK) return s;
+        result = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, lane_stream[lane])
+                                             : launch_group<SOAR_FP32>(b, wg, params->method, lane_stream[lane]);
         i = j;
     }
-    return SOAR_OK;
+    if (lanes > 1) {
+        // always join, also after a failed launch, so that the caller's stream stays ordered
+        if (hipEventRecord(ev_join, lane_stream[1]) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess)
+            result = SOAR_ERR_HIP;
+        (void)hipEventDestroy(ev_fork);
+        (void)hipEventDestroy(ev_join);
+    }
+    return result;
 }
 
 }  // namespace
@@ -993,6 +1054,7 @@ void soar_default_params(soar_params *p)
     p->early_stop_rel = 1e-3f;
     p->search_mode = SOAR_SEARCH_AUTO;
     p->tiles_per_wg = 0;
+    p->streams = 0;
 }
 
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)

@@ -61,7 +61,7 @@ def test_host_side_argument_validation():
     assert _q(p, d_w=0x1008) == 7 and _q(p, ld=68) == 7 and _q(p, codes=0x2004) == 7
     assert _q(p, ws=0) == 5 and _q(p, ws=0x10010) == 5 and _q(p, ws_bytes=1000) == 5
     for field, bad in (("method", 7), ("block", 32), ("iters", 2), ("dss_radius", -1), ("dss_radius", 200),
-                       ("n_beta", 101), ("beta_lo", 0.5), ("search_mode", 9), ("tiles_per_wg", 3),
+                       ("n_beta", 101), ("beta_lo", 0.5), ("search_mode", 9), ("tiles_per_wg", 3), ("streams", 3),
                        ("struct_size", 4)):
         q = B.soar_default_params()
         setattr(q, field, bad)

@@ -6,6 +6,7 @@ expected to be bit-identical, because the tensor-wide sums follow one fixed
 binary64 tree on both sides).
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -244,3 +245,89 @@ def test_closed_form_tensor_round_trips_exactly():
         assert np.array_equal(o.scales.cpu().numpy(), dcode)
         assert o.global_scale.item() == 2.0 ** -6 and o.sse.item() == 0.0
         assert torch.equal(B.dequantize(o, torch.bfloat16), w)
+
+
+# ----------------------------------------------------------------- full-size workloads, bench launch configuration
+def _alloc_out(s):
+    return B.Quantized(torch.empty((s.rows, s.cols // 2), dtype=torch.uint8, device=DEV),
+                       torch.empty((s.rows, s.cols // 16), dtype=torch.uint8, device=DEV),
+                       torch.empty(1, dtype=torch.float32, device=DEV),
+                       torch.empty(1, dtype=torch.float64, device=DEV),
+                       torch.empty(1, dtype=torch.int32, device=DEV))
+
+
+def _compare_tensor(spec, w, o, what):
+    ref = oracle.quantize(np_weights(w), oracle.METHOD_SOAR, spec.dss_radius)
+    assert np.array_equal(o.scales.cpu().numpy(), ref.scales), what
+    assert np.array_equal(o.codes.cpu().numpy(), ref.codes), what
+    assert np.float32(o.global_scale.item()) == ref.global_scale, what
+    assert math.isclose(float(o.sse.item()), ref.sse, rel_tol=REL), what
+    return ref
+
+
+def test_full_model_workload_in_bench_configuration():
+    """All 252 tensors of the 8B-class model through soar_quantize_batch exactly as
+    bench.py enqueues them; every tensor is compared with the oracle byte for byte
+    and checked through properties that hold at any size."""
+    specs = synth.workload_specs(4)
+    weights = [synth.make_weight(s, DEV) for s in specs]
+    outs = [_alloc_out(s) for s in specs]
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, 4)
+    descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+    ws = B.new_batch_workspace(descs, p, DEV)
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    for k in range(len(specs)):
+        _compare_tensor(specs[k], weights[k], outs[k], specs[k].name)
+    # every tensor: valid bytes, error reported == error recomputed from the stored outputs
+    for s, w, o in zip(specs, weights, outs):
+        assert int(o.status.item()) == 0, s.name
+        assert math.isclose(float(B.recon_error(w, o).item()), float(o.sse.item()), rel_tol=1e-9), s.name
+    smin = min(int(o.scales.min().item()) for o in outs)
+    smax = max(int(o.scales.max().item()) for o in outs)
+    assert smin >= 1 and smax <= 0x7E
+    # the single-stream schedule and the exhaustive search give the same bytes
+    outs2 = [_alloc_out(s) for s in specs]
+    p2 = B.soar_default_params(B.SOAR_METHOD_SOAR, 4, B.SOAR_SEARCH_FULL, streams=1)
+    descs2 = [B.make_desc(w, o) for w, o in zip(weights, outs2)]
+    B.quantize_batch(descs2, p2, ws)
+    torch.cuda.synchronize()
+    for s, o, o2 in zip(specs, outs, outs2):
+        assert torch.equal(o.codes, o2.codes) and torch.equal(o.scales, o2.scales), s.name
+        assert o.global_scale.item() == o2.global_scale.item(), s.name
+    # not worse than plain max-based NVFP4 on any tensor of this workload
+    p3 = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
+    sse_soar = [float(o.sse.item()) for o in outs]
+    B.quantize_batch(descs2, p3, ws)
+    torch.cuda.synchronize()
+    for s, e, o2 in zip(specs, sse_soar, outs2):
+        assert e <= float(o2.sse.item()), s.name
+
+
+def _run_70b_layers(first_layer, n_layers):
+    specs = synth.workload_specs(5)[3 * first_layer: 3 * (first_layer + n_layers)]
+    weights = [synth.make_weight(s, DEV) for s in specs]
+    outs = [_alloc_out(s) for s in specs]
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, 8)
+    descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+    ws = B.new_batch_workspace(descs, p, DEV)
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    for s, w, o in zip(specs, weights, outs):
+        _compare_tensor(s, w, o, s.name)
+        assert int(o.status.item()) == 0
+        assert math.isclose(float(B.recon_error(w, o).item()), float(o.sse.item()), rel_tol=1e-9), s.name
+
+
+def test_70b_class_layers_full_size():
+    """Four layers (12 tensors of 2.3e8 weights each, radius 8) of the 70B-class
+    workload as one batch, every tensor compared with the oracle in full."""
+    _run_70b_layers(0, 4)
+
+
+@pytest.mark.skipif(os.environ.get("SOAR_FULL_PARITY") != "1",
+                    reason="all 80 layers (5.6e10 weights) take several minutes: set SOAR_FULL_PARITY=1")
+def test_70b_class_all_layers_full_size():
+    for layer in range(4, 80, 4):
+        print(f"layers {layer}..{layer + 3}", flush=True)
+        _run_70b_layers(layer, 4)
