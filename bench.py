@@ -25,6 +25,10 @@ BYTES_3PASS = 6.5625           # per bf16 weight: three reads + codes + scales
 BYTES_SEARCH = 2.5625          # search kernel alone: one read + codes + scales
 BYTES_STATS = 2.0
 BYTES_ABSMAX = 2.0
+# HBM bytes per weight the search kernel really moves on the full-model workload, from
+# rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
+# (profiles/config4_hbm_traffic_pmc.md): 2.3761 read + 0.5668 written.
+SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.3761 + 0.5668
 
 
 def parse_args():
@@ -128,9 +132,15 @@ def main():
         B.soar_kernel_timing_enable(False)
         dom = max(("absmax", "stats", "search"), key=lambda k: kernels[k]["total_ms"])
         achieved = kernels[dom]["GBps"]
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                    "bytes_per_weight": per_elem[dom], "avg_launch_us": kernels[dom]["avg_us"]}
+        traffic = None
+        if dom == "search" and args.workload == 4 and not args.layers:
+            traffic = SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
+        roofline = {"kernel": "k_" + dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "algorithmic_bytes_per_weight": per_elem[dom],
+                    "weights_per_launch": E / (kernels[dom]["launches"] / n_prof),
+                    "avg_launch_us": kernels[dom]["avg_us"],
+                    "note": "per-launch HIP-event durations on the launch stream, single-stream pass"}
 
     # ---- "MSE vs RTN": the plain max-based NVFP4 of Sec. 3.1 on the same tensors
     p_rtn = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
@@ -143,7 +153,7 @@ def main():
     if not args.no_cpu_baseline:
         import numpy as np
         import oracle
-        sample = specs[:per_layer] if args.workload in (4, 5) else specs[:1]
+        sample = specs[: 2 * per_layer] if args.workload in (4, 5) else specs[:1]
         if args.workload == 5:
             sample = specs[:1]
         host = [w.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) for w in weights[: len(sample)]]
