@@ -365,15 +365,30 @@ __global__ __launch_bounds__(kWG) void k_init(char *slots_base)
 
 // max |w| over a tensor.  |bits| of finite floats order like the values; NaN
 // and Inf patterns are larger than every finite one, so they surface in the max.
+// For bf16 the running maximum stays packed (two 16-bit magnitudes per register,
+// packed integer max) and is unpacked once per lane; for fp32 it is a plain max.
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    u16x2 x, y;
+    __builtin_memcpy(&x, &a, 4);
+    __builtin_memcpy(&y, &b, 4);
+    x = __builtin_elementwise_max(x, y);
+    uint32_t r;
+    __builtin_memcpy(&r, &x, 4);
+    return r;
+}
+
 template <int DT>
-__device__ __forceinline__ uint32_t absmax16(uint4 v)
+__device__ __forceinline__ uint32_t absmax_accumulate(uint32_t m, uint4 v)
 {
     if constexpr (DT == SOAR_BF16) {
-        uint32_t a0 = v.x & 0x7FFF7FFFu, a1 = v.y & 0x7FFF7FFFu, a2 = v.z & 0x7FFF7FFFu, a3 = v.w & 0x7FFF7FFFu;
-        uint32_t m = max(max(a0 & 0xFFFFu, a0 >> 16), max(a1 & 0xFFFFu, a1 >> 16));
-        return max(m, max(max(a2 & 0xFFFFu, a2 >> 16), max(a3 & 0xFFFFu, a3 >> 16)));
+        const uint32_t k = 0x7FFF7FFFu;
+        return pk_max_u16(pk_max_u16(m, pk_max_u16(v.x & k, v.y & k)), pk_max_u16(v.z & k, v.w & k));
     } else {
-        return max(max(v.x & 0x7FFFFFFFu, v.y & 0x7FFFFFFFu), max(v.z & 0x7FFFFFFFu, v.w & 0x7FFFFFFFu));
+        const uint32_t k = 0x7FFFFFFFu;
+        return max(max(m, max(v.x & k, v.y & k)), max(v.z & k, v.w & k));
     }
 }
 
@@ -396,9 +411,9 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
         const size_t off = block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
         const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(t.w) + off);
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) m = max(m, absmax16<DT>(p[c]));
+        for (int c = 0; c < kChunks; ++c) m = absmax_accumulate<DT>(m, p[c]);
     }
-    if constexpr (DT == SOAR_BF16) m <<= 16;
+    if constexpr (DT == SOAR_BF16) m = max(m & 0xFFFFu, m >> 16) << 16;
     m = wave_max_u32(m);
     if ((tid & 63) == 0) s_wave[tid >> 6] = m;
     __syncthreads();
@@ -589,7 +604,9 @@ __device__ __forceinline__ bool search_certified(const float w[16], const float 
     const float sb = alpha1 * e4m3_value((uint32_t)kb);
     const float fa = block_error(w, q, sa);
     const float fb = block_error(w, q, sb);
-    const bool b_wins = (fb < fa) || (fb == fa && search_rank(kb, centre) < search_rank(ka, centre));
+    // ka <= kb <= ka + 1.  In the order 0,-1,+1,-2,+2,... the upper of two adjacent codes comes
+    // first exactly when the lower one lies below the centre.
+    const bool b_wins = (fb < fa) || (fb == fa && ka < centre);
     best = b_wins ? kb : ka;
     best_err = b_wins ? fb : fa;
     const bool left_ok = (ka == wmin) || (sa * (1.0f + 0x1p-17f) <= sstar);
