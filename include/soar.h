@@ -90,7 +90,7 @@ void soar_default_params(soar_params *p);
 /*
  * Bytes of device workspace soar_quantize needs for a rows x cols tensor
  * (control words, per-workgroup partial sums of the tensor-wide reductions of
- * Eq. 5, and 6 bytes per block for the block sums carried from the statistics
+ * Eq. 5, and 4 bytes per block for the block ratio a/b carried from the statistics
  * pass to the search pass).  The workspace must be 256-byte aligned; its
  * contents need no initialisation and are undefined afterwards.  Returns 0 on a
  * bad argument.

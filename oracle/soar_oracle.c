@@ -423,13 +423,14 @@ int soar_oracle_quantize(const void *w, int dtype, int64_t rows, int64_t cols, i
         float wv[BLOCK], q1[BLOCK];
         for (int j = 0; j < BLOCK; ++j)
             wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
-        /* Delta*_i = a_i / (alpha1 * b_i); a block whose codes are all zero
-         * leaves 0/0 and keeps its Eq. 1 scale */
+        /* Delta*_i = (sum w q alpha) / (sum q^2 alpha^2) = (a_i / b_i) / alpha1:
+         * two binary32 divisions; a block whose codes are all zero leaves 0/0
+         * and keeps its Eq. 1 scale */
         float delta_star;
         if (b_all[i] == 0.0f)
             delta_star = soar_oracle_e4m3_value(c0_all[i]);
         else
-            delta_star = a_all[i] / (alpha1 * b_all[i]);
+            delta_star = (a_all[i] / b_all[i]) / alpha1;
         const uint8_t centre = soar_oracle_e4m3_project(delta_star);
         /* quantization scale Delta^q = Delta* (not rounded): new assignment */
         assign_codes(wv, alpha1, delta_star, q1);

@@ -83,8 +83,7 @@ struct Task {
     uint32_t *counters;      // [kKernels][kSlots] arrival counters, kSlotStride apart
     uint32_t *slot_max;      // [kSlots] partial maxima of the absmax kernel, kSlotStride apart
     double   *part;          // [3][kMaxPartials] partial sums N, M, error
-    float    *a;             // [nblk] block sum a (or Delta0 where b == 0)
-    uint16_t *b4;            // [nblk] 4 * block sum b (an integer <= 2304)
+    float    *rho;           // [nblk] a / b of the Eq. 1-2 state, or -Delta0 where b == 0
 };
 
 struct Batch {
@@ -443,8 +442,8 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
 // of kStage consecutive tiles are staged in LDS; lane t then folds the kStage
 // adjacent terms t*kStage.. in registers and one wave tree finishes the group,
 // which is the same adjacent-pair tree at a fraction of the cross-lane work.
-// Each block's (a, b) -- or (Delta0, 0) when its codes are all zero -- is kept
-// for the search kernel.
+// Each block's a/b -- or -Delta0 when its codes are all zero -- is kept for the
+// search kernel.
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
 {
@@ -470,20 +469,19 @@ __global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
             const uint32_t i = (tile0 + kg + kk) * kWG + tid;
             double tN = 0.0, tM = 0.0;
             if (i < t.nblk) {
-                float a = 0.0f, b = 0.0f;
+                float rho = 0.0f;
                 if (!degenerate) {
                     float w[16], q[16];
                     uint32_t nib[2], c0;
-                    float delta0;
+                    float delta0, a, b;
                     load_block<DT>(t.w, block_offset(t, i), w);
                     block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
                     block_sums(w, q, a, b);
                     tN = (double)a * (double)delta0;
                     tM = ((double)b * (double)delta0) * (double)delta0;
-                    if (b == 0.0f) a = delta0;
+                    rho = (b == 0.0f) ? -delta0 : a / b;      // first half of Eq. 6
                 }
-                t.a[i] = a;
-                t.b4[i] = (uint16_t)(b * 4.0f);        // exact: b is a multiple of 1/4, at most 576
+                t.rho[i] = rho;
             }
             s_terms[kk * kWG + tid] = make_double2(tN, tM);
         }
@@ -664,9 +662,8 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
             out_code = c0;
             out_err = block_error(w, q, alpha0 * delta0);
         } else {
-            const float a = t.a[i];                    // a, or Delta0 where b == 0
-            const float b = (float)t.b4[i] * 0.25f;
-            const float delta_star = (b == 0.0f) ? a : a / (alpha1 * b);
+            const float rho = t.rho[i];                // a / b >= 0, or -Delta0 where b == 0
+            const float delta_star = (rho < 0.0f) ? -rho : rho / alpha1;
             const int centre = (int)e4m3_project(delta_star);
             assign_codes(w, alpha1 * delta_star, nib, q);
             int best;
@@ -833,11 +830,11 @@ soar_status check_matrix_ptr(const void *p, int dtype, int64_t ld)
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
-// bytes of per-block workspace (a: float, b4: uint16) of one tensor
+// bytes of per-block workspace (one float) of one tensor
 size_t per_block_bytes(int64_t rows, int64_t cols)
 {
     const size_t nblk = (size_t)(rows * (cols / 16));
-    return align256(nblk * sizeof(float)) + align256(nblk * sizeof(uint16_t));
+    return align256(nblk * sizeof(float));
 }
 
 // addressing and launch shape of one tensor; the workspace fields stay unset
@@ -1031,10 +1028,8 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
             t.slot_max = reinterpret_cast<uint32_t *>(slot + kCtrlBytes + kCountersBytes);
             t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
-            t.a = reinterpret_cast<float *>(per_block);
+            t.rho = reinterpret_cast<float *>(per_block);
             per_block += align256((size_t)t.nblk * sizeof(float));
-            t.b4 = reinterpret_cast<uint16_t *>(per_block);
-            per_block += align256((size_t)t.nblk * sizeof(uint16_t));
             b.t[k - i] = t;
         }
         result = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, lane_stream[lane])
