@@ -481,7 +481,7 @@ __global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
                     tM = ((double)b * (double)delta0) * (double)delta0;
                     rho = (b == 0.0f) ? -delta0 : a / b;      // first half of Eq. 6
                 }
-                t.rho[i] = rho;
+                __builtin_nontemporal_store(rho, t.rho + i);
             }
             s_terms[kk * kWG + tid] = make_double2(tN, tM);
         }
@@ -674,8 +674,13 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
             out_code = (uint32_t)best;
             out_err = best_err;
         }
-        reinterpret_cast<uint2 *>(t.codes)[i] = make_uint2(nib[0], nib[1]);
-        t.scales[i] = (uint8_t)out_code;
+        {
+            // streaming stores: the outputs are not read again by this path
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            u32x2 packed = {nib[0], nib[1]};
+            __builtin_nontemporal_store(packed, reinterpret_cast<u32x2 *>(t.codes) + i);
+            __builtin_nontemporal_store((uint8_t)out_code, t.scales + i);
+        }
         sse += (double)out_err;
     }
     // error sum: fixed order for a given launch shape
