@@ -142,8 +142,8 @@ typedef struct {
  * soar_quantize_batch -- soar_quantize for n tensors (the linear layers of a
  * model, Sec. 4.1) on one stream with one shared workspace of at least
  * soar_batch_workspace_bytes().  Consecutive tensors of one element type are
- * served by the same kernel launches (up to 8 tensors and 2^28 weights per
- * launch), each tensor with its own tensor-wide reductions; results are those
+ * served by the same kernel launches (up to 8 tensors and 256 MiB of weights
+ * per launch), each tensor with its own tensor-wide reductions; results are those
  * of n separate soar_quantize calls.  `descs` is HOST memory and is not
  * referenced after the call returns.  All descriptors are validated before
  * anything is enqueued.

@@ -38,7 +38,8 @@ constexpr int kWG = 256;                 // lanes per workgroup = blocks per til
 constexpr int kStage = 4;                // tiles whose block terms are staged in LDS per tree step
 constexpr int kMaxPartials = 16384;      // workgroups per tensor, at most
 constexpr int kGroupMax = 8;             // tensors per launch
-constexpr int64_t kGroupElemCap = (int64_t)1 << 28;   // weights per launch (beyond the first tensor)
+constexpr int64_t kGroupByteCap = (int64_t)1 << 28;   // bytes of weights per launch (beyond the first tensor):
+                                                      // a group then fits the 256 MiB last-level cache between passes
 constexpr int kSlots = 64;               // first-level arrival counters
 constexpr int kSlotStride = 32;          // in uint32: one counter per 128 bytes
 constexpr int kKernels = 3;              // absmax, stats, search
@@ -137,12 +138,26 @@ __device__ __forceinline__ void fp4x8_values(uint32_t r, float *q)
 }
 
 // ------------------------------------------------------------------ loads
-template <int DT>
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// The first two passes read the weights with ordinary loads, so that a launch group (at most
+// 256 MiB) stays in the last-level cache for the pass that follows; the search pass, the last
+// reader, streams them.
+constexpr bool kStreamAbsmax = false, kStreamStats = false, kStreamSearch = true;
+
+// 16 bytes; STREAM = nontemporal (no reuse expected by this kernel)
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load16(const void *p)
+{
+    if constexpr (STREAM) return __builtin_nontemporal_load(static_cast<const u32x4 *>(p));
+    else return *static_cast<const u32x4 *>(p);
+}
+
+template <int DT, bool STREAM = false>
 __device__ __forceinline__ void load_block(const void *base, size_t elem_off, float w[16])
 {
     if constexpr (DT == SOAR_BF16) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + elem_off);
-        uint4 v0 = p[0], v1 = p[1];
+        const uint16_t *p = static_cast<const uint16_t *>(base) + elem_off;
+        const u32x4 v0 = load16<STREAM>(p), v1 = load16<STREAM>(p + 8);
         uint32_t u[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -150,11 +165,11 @@ __device__ __forceinline__ void load_block(const void *base, size_t elem_off, fl
             w[2 * k + 1] = f_of(u[k] & 0xFFFF0000u);
         }
     } else {
-        const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(base) + elem_off);
+        const float *p = static_cast<const float *>(base) + elem_off;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            float4 v = p[k];
-            w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+            const u32x4 v = load16<STREAM>(p + 4 * k);
+            w[4 * k] = f_of(v.x); w[4 * k + 1] = f_of(v.y); w[4 * k + 2] = f_of(v.z); w[4 * k + 3] = f_of(v.w);
         }
     }
 }
@@ -347,10 +362,11 @@ __device__ double tree_of_partials(const double *part, uint32_t P, double *lds /
 // which tensor of the launch this workgroup works on, and its index there
 __device__ __forceinline__ uint32_t find_task(const Batch &b, uint32_t &lwg)
 {
+    const uint32_t id = blockIdx.x;
     uint32_t k = 0;
     for (uint32_t j = 1; j < b.n; ++j)
-        if (blockIdx.x >= b.t[j].wg_begin) k = j;
-    lwg = blockIdx.x - b.t[k].wg_begin;
+        if (id >= b.t[j].wg_begin) k = j;
+    lwg = id - b.t[k].wg_begin;
     return k;
 }
 
@@ -408,9 +424,12 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
         const uint32_t i = (k * t.n_wg + lwg) * kWG + tid;
         if (i >= t.nblk) break;
         const size_t off = block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
-        const uint4 *p = reinterpret_cast<const uint4 *>(static_cast<const char *>(t.w) + off);
+        const char *p = static_cast<const char *>(t.w) + off;
 #pragma unroll
-        for (int c = 0; c < kChunks; ++c) m = absmax_accumulate<DT>(m, p[c]);
+        for (int c = 0; c < kChunks; ++c) {
+            const u32x4 v = load16<kStreamAbsmax>(p + 16 * c);
+            m = absmax_accumulate<DT>(m, make_uint4(v.x, v.y, v.z, v.w));
+        }
     }
     if constexpr (DT == SOAR_BF16) m = max(m & 0xFFFFu, m >> 16) << 16;
     m = wave_max_u32(m);
@@ -474,7 +493,7 @@ __global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
                     float w[16], q[16];
                     uint32_t nib[2], c0;
                     float delta0, a, b;
-                    load_block<DT>(t.w, block_offset(t, i), w);
+                    load_block<DT, kStreamStats>(t.w, block_offset(t, i), w);
                     block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
                     block_sums(w, q, a, b);
                     tN = (double)a * (double)delta0;
@@ -643,7 +662,7 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
         if (i >= t.nblk) break;
         float w[16], q[16];
         uint32_t nib[2];
-        load_block<DT>(t.w, block_offset(t, i), w);
+        load_block<DT, kStreamSearch>(t.w, block_offset(t, i), w);
         uint32_t out_code;
         float out_err;
         if (allzero) {
@@ -662,7 +681,7 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
             out_code = c0;
             out_err = block_error(w, q, alpha0 * delta0);
         } else {
-            const float rho = t.rho[i];                // a / b >= 0, or -Delta0 where b == 0
+            const float rho = __builtin_nontemporal_load(t.rho + i);                // a / b >= 0, or -Delta0 where b == 0
             const float delta_star = (rho < 0.0f) ? -rho : rho / alpha1;
             const int centre = (int)e4m3_project(delta_star);
             assign_codes(w, alpha1 * delta_star, nib, q);
@@ -881,13 +900,15 @@ soar_status validate_tensor(const soar_tensor_desc &d, const soar_params *params
 }
 
 // how many tensors starting at `first` go into one launch
+int64_t weight_bytes(const soar_tensor_desc &d) { return d.rows * d.cols * (d.dtype == SOAR_BF16 ? 2 : 4); }
+
 int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
 {
-    int64_t elems = descs[first].rows * descs[first].cols;
+    int64_t bytes = weight_bytes(descs[first]);
     int32_t j = first + 1;
     while (j < n && j - first < kGroupMax && descs[j].dtype == descs[first].dtype &&
-           elems + descs[j].rows * descs[j].cols <= kGroupElemCap) {
-        elems += descs[j].rows * descs[j].cols;
+           bytes + weight_bytes(descs[j]) <= kGroupByteCap) {
+        bytes += weight_bytes(descs[j]);
         ++j;
     }
     return j;
