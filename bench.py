@@ -27,8 +27,8 @@ BYTES_STATS = 2.0
 BYTES_ABSMAX = 2.0
 # HBM bytes per weight the search kernel really moves on the full-model workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
-# (profiles/config4_hbm_traffic_pmc.md): 2.3761 read + 0.5668 written.
-SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.3761 + 0.5668
+# (profiles/config4_hbm_traffic_pmc.md): 2.2552 read + 0.5827 written.
+SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2552 + 0.5827
 
 
 def parse_args():
