@@ -21,7 +21,8 @@ METHOD_RTN, METHOD_SOAR = 0, 1
 STATUS_NONFINITE, STATUS_ALLZERO = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsoar_oracle.so")
+# SOAR_ORACLE_LIB lets the mutation test point the pins at a deliberately broken build
+_LIB_PATH = os.environ.get("SOAR_ORACLE_LIB") or os.path.join(_HERE, "libsoar_oracle.so")
 _lib = None
 
 

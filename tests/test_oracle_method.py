@@ -235,6 +235,34 @@ def test_dss_choice_against_enumeration_of_all_e4m3_scales(case):
     assert math.isclose(so.sse, float(e_chosen.sum()), rel_tol=1e-5)
 
 
+@pytest.mark.parametrize("K", [0, 1, 2])
+def test_dss_small_radius_uses_the_whole_window(K):
+    """With a small radius the best code often sits on the edge of the window:
+    the choice must still be the best of centre-K..centre+K, and for K = 1 both
+    edges must be taken by some block."""
+    spec, w = weights(2, 16)
+    bits = synth.bf16_bits(w)
+    out = oracle.quantize(bits, oracle.METHOD_SOAR, K, want_trace=True)
+    wb = w.double().numpy().reshape(-1, 16)
+    q1 = unpack(out.codes).reshape(-1, 16)
+    s = float(out.trace["alpha1"]) * E4M3[1:0x7F]
+    A = (wb * wb).sum(axis=1)[:, None]
+    Bq = (wb * q1).sum(axis=1)[:, None]
+    Cq = (q1 * q1).sum(axis=1)[:, None]
+    err = A - 2 * Bq * s[None, :] + Cq * s[None, :] ** 2
+    centre = out.trace["centre"].astype(np.int64)
+    chosen = out.scales.reshape(-1).astype(np.int64)
+    allc = np.arange(1, 0x7F)
+    inwin = (allc[None, :] >= (centre - K)[:, None]) & (allc[None, :] <= (centre + K)[:, None])
+    e_win = np.where(inwin, err, np.inf).min(axis=1)
+    e_chosen = err[np.arange(len(chosen)), chosen - 1]
+    assert np.all(np.abs(chosen - centre) <= K)
+    assert np.all(e_chosen <= e_win + 2e-6 * A[:, 0])
+    if K == 1:      # +-1 is chosen by about one block in ten; +-2 by one in ten thousand
+        off = chosen - centre
+        assert (off == -K).any() and (off == K).any()
+
+
 def test_dss_exact_tie_prefers_the_centre_code():
     """A block whose codes are all zero has the same error for every candidate:
     the first in search order, the centre, must be kept."""
