@@ -37,6 +37,11 @@ class _Trace(C.Structure):
     ]
 
 
+class _IterParams(C.Structure):
+    _fields_ = [("iters", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float), ("beta_hi", C.c_float),
+                ("dd_mode", C.c_int32), ("dss_radius", C.c_int32), ("early_stop_rel", C.c_float)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -63,6 +68,11 @@ def lib():
             C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int,
             C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double),
             C.POINTER(C.c_int32), C.POINTER(_Trace)]
+        L.soar_oracle_quantize_iter.restype = C.c_int
+        L.soar_oracle_quantize_iter.argtypes = [
+            C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.POINTER(_IterParams),
+            C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double),
+            C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
         L.soar_oracle_dequantize.restype = C.c_int
         L.soar_oracle_dequantize.argtypes = [
             C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
@@ -189,6 +199,31 @@ def quantize(w: np.ndarray, method: int = METHOD_SOAR, dss_radius: int = 4,
         trace = dict(bufs)
         trace.update(alpha0=np.float32(tr.alpha0), alpha1=np.float32(tr.alpha1), N=tr.N, M=tr.M)
     return Quantized(codes, scales, np.float32(g.value), float(sse.value), int(st.value), trace)
+
+
+DD_WINDOW, DD_BRACKET = 0, 1
+
+
+def quantize_iter(w: np.ndarray, iters: int = 15, n_beta: int = 101, beta_lo: float = 0.5,
+                  beta_hi: float = 1.5, dd_mode: int = DD_BRACKET, dss_radius: int = 1,
+                  early_stop_rel: float = 1e-3) -> Quantized:
+    """Algorithm 1 in full (defaults: the paper's settings).  The returned trace holds
+    ``sse_trace`` (error of the Eq. 1-2 state, then after every iteration run) and
+    ``iters_run``."""
+    rows, cols, ld = _check2d(w)
+    dt = _dtype_of(w)
+    codes = np.zeros((rows, cols // 2), dtype=np.uint8)
+    scales = np.zeros((rows, cols // 16), dtype=np.uint8)
+    g, sse, st, it = C.c_float(0.0), C.c_double(0.0), C.c_int32(0), C.c_int32(0)
+    tracebuf = np.full(iters + 1, np.nan, dtype=np.float64)
+    p = _IterParams(iters, n_beta, beta_lo, beta_hi, dd_mode, dss_radius, early_stop_rel)
+    rc = lib().soar_oracle_quantize_iter(w.ctypes.data, dt, rows, cols, ld, C.byref(p), codes.ctypes.data,
+                                         scales.ctypes.data, C.byref(g), C.byref(sse), C.byref(st),
+                                         C.byref(it), tracebuf.ctypes.data)
+    if rc != 0:
+        raise ValueError("soar_oracle_quantize_iter: bad argument")
+    return Quantized(codes, scales, np.float32(g.value), float(sse.value), int(st.value),
+                     dict(sse_trace=tracebuf, iters_run=int(it.value)))
 
 
 def dequantize(codes: np.ndarray, scales: np.ndarray, global_scale, out_dtype: int = FP32) -> np.ndarray:

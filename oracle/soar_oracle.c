@@ -462,6 +462,208 @@ int soar_oracle_quantize(const void *w, int dtype, int64_t rows, int64_t cols, i
     return 0;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Algorithm 1 in full: T iterations, beta grid, early stop                     */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t iters;           /* T of Algorithm 1 (the paper uses 15)                       */
+    int32_t n_beta;          /* size of the quantization-scale grid (paper: 101)           */
+    float   beta_lo;         /* paper: 0.5                                                 */
+    float   beta_hi;         /* paper: 1.5                                                 */
+    int32_t dd_mode;         /* 0: E4M3 codes centre-K..centre+K around the rounded Eq. 6
+                                scale; 1: the two representable values that surround it
+                                (Appendix B.3)                                             */
+    int32_t dss_radius;      /* K of dd_mode 0                                             */
+    float   early_stop_rel;  /* stop when the relative drop of the error is below this
+                                (paper: 1e-3); <= 0 never stops                            */
+} soar_oracle_iter_params;
+
+/* largest E4M3 code in [0x01, 0x7E] whose value does not exceed y (0x01 if none) */
+static int e4m3_floor_code(float y)
+{
+    int best = E4M3_CODE_MIN;
+    for (int c = E4M3_CODE_MIN; c <= E4M3_CODE_MAX; ++c)
+        if (soar_oracle_e4m3_value((uint8_t)c) <= y) best = c;
+    return best;
+}
+
+/* beta_k of the grid: lo and hi are hit exactly, and so is 1 on the paper's grid */
+static float beta_of(const soar_oracle_iter_params *p, int k)
+{
+    if (p->n_beta <= 1) return p->beta_lo;
+    return (p->beta_lo * (float)(p->n_beta - 1 - k) + p->beta_hi * (float)k) / (float)(p->n_beta - 1);
+}
+
+/*
+ * soar_oracle_quantize_iter -- Algorithm 1 as printed: initialisation by Eq. 1
+ * with Delta^q = Delta^d; then T times
+ *     Q      = Q_FP4(W / (alpha Delta^q))                         (Eq. 2)
+ *     alpha <- sum W Q Delta^d / sum Q^2 (Delta^d)^2              (Eq. 5)
+ *     Delta* = (sum W Q / sum Q^2) / alpha                        (Eq. 6)
+ *     D^d    = E4M3 candidates near Delta*,  D^q = {Delta* beta}  (Sec. 3.3 (ii), App. B.3)
+ *     (Delta^q, Delta^d) <- argmin over D^q x D^d of Eq. 8
+ * with early stopping on the relative drop of the total error, and the final
+ * reconstruction Q_FP4(W/(alpha Delta^q)) * (alpha Delta^d).
+ *
+ * Candidate pairs are tried with beta ascending and, for each beta, the stored
+ * scales in the order "centre, -1, +1, -2, ..." (dd_mode 0) or "lower, upper"
+ * (dd_mode 1); a later pair wins only if strictly better in binary32.  All
+ * per-block and tensor-wide arithmetic is that of soar_oracle_quantize; with
+ * iters = 1, n_beta = 1, beta = 1, dd_mode = 0 the two functions agree bit
+ * for bit.
+ *
+ * sse_trace (may be NULL): iters+1 doubles; [0] is the error of the Eq. 1-2
+ * state, [t+1] the error after iteration t; entries after an early stop are
+ * left untouched.  iters_run (may be NULL): iterations carried out.
+ */
+int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                              const soar_oracle_iter_params *p,
+                              uint8_t *codes, uint8_t *scales, float *global_scale,
+                              double *sse, int32_t *status, int32_t *iters_run, double *sse_trace)
+{
+    if (!w || !codes || !scales || !global_scale || !p) return -1;
+    if (rows <= 0 || cols <= 0 || cols % BLOCK != 0 || ld < cols) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32) return -1;
+    if (p->iters < 1 || p->n_beta < 1 || p->n_beta > 4096) return -1;
+    if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo)) return -1;
+    if (p->dd_mode != 0 && p->dd_mode != 1) return -1;
+    if (p->dss_radius < 0 || p->dss_radius > 125) return -1;
+
+    const int64_t bpr = cols / BLOCK;
+    const int64_t nblk = rows * bpr;
+
+    float amax = 0.0f;
+    int nonfinite = 0;
+#pragma omp parallel for schedule(static) reduction(max : amax) reduction(| : nonfinite)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) {
+            float v = load_w(w, dtype, r * ld + c);
+            if (!isfinite(v)) nonfinite = 1;
+            else if (fabsf(v) > amax) amax = fabsf(v);
+        }
+    if (nonfinite || amax == 0.0f) {
+        /* degenerate tensors behave as in the single-step function */
+        if (iters_run) *iters_run = 0;
+        return soar_oracle_quantize(w, dtype, rows, cols, ld, ORACLE_METHOD_SOAR, 0, codes, scales,
+                                    global_scale, sse, status, NULL);
+    }
+
+    float *dq = (float *)malloc(sizeof(float) * (size_t)nblk);       /* Delta^q */
+    uint8_t *dd = (uint8_t *)malloc((size_t)nblk);                   /* code of Delta^d */
+    float *a_all = (float *)malloc(sizeof(float) * (size_t)nblk);
+    float *b_all = (float *)malloc(sizeof(float) * (size_t)nblk);
+    double *termN = (double *)malloc(sizeof(double) * (size_t)nblk);
+    double *termM = (double *)malloc(sizeof(double) * (size_t)nblk);
+    double *errs = (double *)malloc(sizeof(double) * (size_t)nblk);
+    if (!dq || !dd || !a_all || !b_all || !termN || !termM || !errs) {
+        free(dq); free(dd); free(a_all); free(b_all); free(termN); free(termM); free(errs);
+        return -1;
+    }
+
+    /* ---- initialisation: Eq. 1, Delta^q = Delta^d; error of the Eq. 1-2 state ---- */
+    float alpha = amax / (M_FP4 * M_FP8);
+    const float alpha0_m = alpha * M_FP4;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nblk; ++i) {
+        int64_t r = i / bpr, cb = i % bpr;
+        float wv[BLOCK], q0[BLOCK];
+        float bmax = 0.0f;
+        for (int j = 0; j < BLOCK; ++j) {
+            wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
+            if (fabsf(wv[j]) > bmax) bmax = fabsf(wv[j]);
+        }
+        dd[i] = soar_oracle_e4m3_project(bmax / alpha0_m);
+        dq[i] = soar_oracle_e4m3_value(dd[i]);
+        assign_codes(wv, alpha, dq[i], q0);
+        errs[i] = (double)block_error(wv, q0, alpha * dq[i]);
+    }
+    double prev = tree_sum(errs, nblk);
+    if (sse_trace) sse_trace[0] = prev;
+
+    int done = 0;
+    double cur = prev;
+    for (int t = 0; t < p->iters; ++t) {
+        /* ---- Q under the current scales, block sums, Eq. 5 ---- */
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < nblk; ++i) {
+            int64_t r = i / bpr, cb = i % bpr;
+            float wv[BLOCK], q[BLOCK];
+            for (int j = 0; j < BLOCK; ++j) wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
+            assign_codes(wv, alpha, dq[i], q);
+            block_sums(wv, q, &a_all[i], &b_all[i]);
+            float d = soar_oracle_e4m3_value(dd[i]);
+            termN[i] = (double)a_all[i] * (double)d;
+            termM[i] = ((double)b_all[i] * (double)d) * (double)d;
+        }
+        const double N = tree_sum(termN, nblk);
+        const double M = tree_sum(termM, nblk);
+        const float alpha_new = (M > 0.0) ? (float)(N / M) : alpha;
+
+        /* ---- Eq. 6 and the joint search of Sec. 3.3 ---- */
+#pragma omp parallel for schedule(static)
+        for (int64_t i = 0; i < nblk; ++i) {
+            int64_t r = i / bpr, cb = i % bpr;
+            float wv[BLOCK], q[BLOCK], qbest[BLOCK];
+            for (int j = 0; j < BLOCK; ++j) wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
+            float delta_star;
+            if (b_all[i] == 0.0f)
+                delta_star = soar_oracle_e4m3_value(dd[i]);
+            else
+                delta_star = (a_all[i] / b_all[i]) / alpha_new;
+            /* stored-scale candidates */
+            int cand[256], ncand = 0;
+            if (p->dd_mode == 0) {
+                int centre = soar_oracle_e4m3_project(delta_star);
+                cand[ncand++] = centre;
+                for (int k = 1; k <= p->dss_radius; ++k)
+                    for (int sgn = -1; sgn <= 1; sgn += 2) {
+                        int c = centre + sgn * k;
+                        if (c >= E4M3_CODE_MIN && c <= E4M3_CODE_MAX) cand[ncand++] = c;
+                    }
+            } else {
+                int lo = e4m3_floor_code(delta_star);
+                cand[ncand++] = lo;
+                if (lo < E4M3_CODE_MAX) cand[ncand++] = lo + 1;
+            }
+            int have = 0, best_code = cand[0];
+            float best_err = 0.0f, best_dq = delta_star;
+            for (int k = 0; k < p->n_beta; ++k) {
+                float dq_k = delta_star * beta_of(p, k);
+                assign_codes(wv, alpha_new, dq_k, q);
+                for (int c = 0; c < ncand; ++c) {
+                    float err = block_error(wv, q, alpha_new * soar_oracle_e4m3_value((uint8_t)cand[c]));
+                    if (!have || err < best_err) {
+                        have = 1;
+                        best_err = err;
+                        best_code = cand[c];
+                        best_dq = dq_k;
+                        memcpy(qbest, q, sizeof qbest);
+                    }
+                }
+            }
+            dq[i] = best_dq;
+            dd[i] = (uint8_t)best_code;
+            errs[i] = (double)best_err;
+            pack_block(wv, qbest, codes + i * (BLOCK / 2));
+        }
+        alpha = alpha_new;
+        cur = tree_sum(errs, nblk);
+        if (sse_trace) sse_trace[t + 1] = cur;
+        done = t + 1;
+        /* early stop: relative drop of the error below the threshold */
+        if (p->early_stop_rel > 0.0f && (prev - cur) < (double)p->early_stop_rel * prev) break;
+        prev = cur;
+    }
+    memcpy(scales, dd, (size_t)nblk);
+    *global_scale = alpha;
+    if (sse) *sse = cur;
+    if (status) *status = 0;
+    if (iters_run) *iters_run = done;
+    free(dq); free(dd); free(a_all); free(b_all); free(termN); free(termM); free(errs);
+    return 0;
+}
+
 /*
  * Dequantization, Eq. 3:  w^_ij = q_ij * (alpha * d_i), the combined scale
  * being rounded to binary32 first.  out_dtype BF16 rounds the result to

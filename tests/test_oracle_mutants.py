@@ -16,8 +16,8 @@ MUTANTS = [
     ("e2m1 no saturation", "        r = M_FP4;\n    return copysignf", "        r = 2.0f * rintf(a / 2.0f);\n    return copysignf"),
     ("e4m3 ties up", "rint(v / quantum) * quantum", "floor(v / quantum + 0.5) * quantum"),
     ("e4m3 subnormal spacing", "if (E < -6) E = -6;              /* below", "if (E < -7) E = -7;              /* below"),
-    ("alpha0 without M_FP4", "amax / (M_FP4 * M_FP8)", "amax / M_FP8"),
-    ("block scale without M_FP4", "soar_oracle_e4m3_project(bmax / alpha0_m)", "soar_oracle_e4m3_project(bmax / alpha0)"),
+    ("alpha0 without M_FP4", "const float alpha0 = amax / (M_FP4 * M_FP8);", "const float alpha0 = amax / M_FP8;"),
+    ("block scale without M_FP4", "uint8_t c0 = soar_oracle_e4m3_project(bmax / alpha0_m);", "uint8_t c0 = soar_oracle_e4m3_project(bmax / alpha0);"),
     ("error with wrong sign", "float e = fmaf(-q[j], s, wv[j]);", "float e = fmaf(q[j], s, wv[j]);"),
     ("Eq. 5 denominator with Delta instead of Delta^2",
      "termM[i] = ((double)b * (double)delta0) * (double)delta0;", "termM[i] = (double)b * (double)delta0;"),
@@ -28,7 +28,7 @@ MUTANTS = [
     ("later candidate wins ties", "if (err < best_err) { best_err = err; best_code = c; }",
      "if (err <= best_err) { best_err = err; best_code = c; }"),
     ("window one code short", "for (int k = 1; k <= dss_radius; ++k) {", "for (int k = 1; k < dss_radius; ++k) {"),
-    ("search only upwards", "for (int sgn = -1; sgn <= 1; sgn += 2) {", "for (int sgn = 1; sgn <= 1; sgn += 2) {"),
+    ("search only upwards", "++k) {\n            for (int sgn = -1; sgn <= 1; sgn += 2) {", "++k) {\n            for (int sgn = 1; sgn <= 1; sgn += 2) {"),
     ("nibbles swapped", "out[k] = (uint8_t)(lo | (hi << 4));", "out[k] = (uint8_t)(hi | (lo << 4));"),
     ("codes from the rounded scale (not decoupled)", "assign_codes(wv, alpha1, delta_star, q1);",
      "assign_codes(wv, alpha1, soar_oracle_e4m3_value(centre), q1);"),
@@ -42,6 +42,27 @@ MUTANTS = [
      "errs[i] = (double)block_error(wv, q, global_scale * soar_oracle_e4m3_value(scales[(i % bpr) * rows + i / bpr < nblk ? (i % bpr) * rows + i / bpr : i]));"),
 ]
 
+# mistakes in the iterated form of Algorithm 1 (caught by tests/test_oracle_iter.py)
+MUTANTS += [
+    ("iter: Eq. 5 with the search scale instead of the stored one",
+     "float d = soar_oracle_e4m3_value(dd[i]);\n            termN[i]", "float d = dq[i];\n            termN[i]"),
+    ("iter: codes from the previous global scale", "assign_codes(wv, alpha_new, dq_k, q);", "assign_codes(wv, alpha, dq_k, q);"),
+    ("iter: beta grid one step short", "return (p->beta_lo * (float)(p->n_beta - 1 - k) + p->beta_hi * (float)k) / (float)(p->n_beta - 1);",
+     "return (p->beta_lo * (float)(p->n_beta - 1 - k) + p->beta_hi * (float)k) / (float)(p->n_beta);"),
+    ("iter: bracket takes the code above only", "if (lo < E4M3_CODE_MAX) cand[ncand++] = lo + 1;", "if (lo < E4M3_CODE_MAX) cand[ncand - 1] = lo + 1;"),
+    ("iter: floor code off by one", "int lo = e4m3_floor_code(delta_star);", "int lo = e4m3_floor_code(delta_star) - 1; if (lo < E4M3_CODE_MIN) lo = E4M3_CODE_MIN;"),
+    ("iter: search scale not kept", "dq[i] = best_dq;", "dq[i] = delta_star;"),
+    ("iter: stored scale not kept", "dd[i] = (uint8_t)best_code;", "dd[i] = (uint8_t)cand[0];"),
+    ("iter: early stop on the absolute drop", "(prev - cur) < (double)p->early_stop_rel * prev) break;", "(prev - cur) < (double)p->early_stop_rel) break;"),
+    ("iter: early stop compares with the first error", "        prev = cur;\n    }\n    memcpy(scales, dd", "    }\n    memcpy(scales, dd"),
+    ("iter: global scale not advanced", "        alpha = alpha_new;\n        cur = tree_sum(errs, nblk);", "        cur = tree_sum(errs, nblk);"),
+    ("iter: Eq. 6 with the previous global scale", "delta_star = (a_all[i] / b_all[i]) / alpha_new;", "delta_star = (a_all[i] / b_all[i]) / alpha;"),
+    ("iter: initial global scale without M_FP4", "float alpha = amax / (M_FP4 * M_FP8);", "float alpha = amax / M_FP8;"),
+    ("iter: initial block scale without M_FP4", "dd[i] = soar_oracle_e4m3_project(bmax / alpha0_m);", "dd[i] = soar_oracle_e4m3_project(bmax / alpha);"),
+    ("iter: window searched upwards only", "++k)\n                    for (int sgn = -1; sgn <= 1; sgn += 2) {", "++k)\n                    for (int sgn = 1; sgn <= 1; sgn += 2) {"),
+    ("iter: trace entry of the wrong iteration", "if (sse_trace) sse_trace[t + 1] = cur;", "if (sse_trace) sse_trace[t + 1] = prev;"),
+]
+
 
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0].replace(" ", "_") for m in MUTANTS])
 def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
@@ -53,9 +74,9 @@ def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
     subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-w",
                     str(c_file), "-o", str(so_file), "-lm"], check=True)
     env = dict(os.environ, SOAR_ORACLE_LIB=str(so_file))
-    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_oracle_formats.py"),
-                        os.path.join(ROOT, "tests", "test_oracle_method.py")],
+    files = ["test_oracle_iter.py"] if name.startswith("iter:") else ["test_oracle_formats.py", "test_oracle_method.py"]
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"]
+                       + [os.path.join(ROOT, "tests", f) for f in files],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     assert r.returncode != 0, f"mutant '{name}' passed every pin:\n{r.stdout[-800:]}"
     assert "failed" in r.stdout or "error" in r.stdout.lower()
