@@ -5,7 +5,9 @@
  * NVFP4 weight quantization (Sec. 3.1) with one Closed-form Joint Scale
  * Optimization step (Sec. 3.2, Eq. 5-6) followed by one Decoupled Scale Search
  * over E4M3 candidates for the stored block scale (Sec. 3.3, Eq. 7-8;
- * Algorithm 1 with T = 1 and beta = 1).
+ * Algorithm 1 with T = 1 and beta = 1) -- the single-step path -- and, through
+ * the same entry points, Algorithm 1 in full: T iterations, a grid of
+ * quantization-scale factors beta, early stopping (the iterated path).
  *
  * Conventions common to all entry points
  *   - every pointer whose name starts with d_ is DEVICE memory owned by the
@@ -59,6 +61,12 @@ typedef enum {
     SOAR_SEARCH_FULL = 1     /* evaluate all 2K+1 candidates                        */
 } soar_search_mode;
 
+/* which E4M3 codes are candidates for the stored scale Delta^d (Sec. 3.3 (ii)) */
+typedef enum {
+    SOAR_DD_WINDOW = 0,      /* centre-K .. centre+K, centre = E4M3(Delta*) (App. D) */
+    SOAR_DD_BRACKET = 1      /* the two codes that enclose Delta* (App. B.3)         */
+} soar_dd_mode;
+
 /* data-dependent status bits written to *d_status */
 #define SOAR_STATUS_NONFINITE 1   /* NaN or Inf in the weights: outputs unspecified  */
 #define SOAR_STATUS_ALLZERO   2   /* every weight is zero                            */
@@ -67,13 +75,17 @@ typedef struct {
     uint32_t struct_size;    /* sizeof(soar_params), for forward compatibility      */
     int32_t  method;         /* soar_method                                         */
     int32_t  block;          /* block size G of Algorithm 1; must be 16             */
-    int32_t  iters;          /* iterations T of Algorithm 1; must be 1              */
+    int32_t  iters;          /* iterations T of Algorithm 1, 1 .. 64                */
     int32_t  dss_radius;     /* K >= 0: stored-scale candidates are the E4M3 codes
                                 centre-K .. centre+K (Sec. 3.3 (ii)); 0 = centre only */
-    int32_t  n_beta;         /* size of the quantization-scale grid; must be 1      */
-    float    beta_lo;        /* must be 1                                           */
-    float    beta_hi;        /* must be 1                                           */
-    float    early_stop_rel; /* unused while iters == 1                             */
+    int32_t  n_beta;         /* size of the grid of quantization-scale factors,
+                                1 .. 4096 (Sec. 3.3 (i); App. B.3 uses 101)          */
+    float    beta_lo;        /* grid ends, 0 < beta_lo <= beta_hi; factor k is
+                                (beta_lo (n-1-k) + beta_hi k) / (n-1) in binary32,   */
+    float    beta_hi;        /* beta_lo alone when n_beta == 1                       */
+    float    early_stop_rel; /* >= 0; the iterated path stops after an iteration that
+                                lowers the error by less than this fraction of the
+                                error before it (App. B.3: 1e-3); 0 = never         */
     int32_t  search_mode;    /* soar_search_mode                                    */
     int32_t  tiles_per_wg;   /* 0 = chosen by the library; a power of two <= 65536
                                 forces how many 256-block tiles one workgroup walks
@@ -82,10 +94,16 @@ typedef struct {
                                 groups alternate between the caller's stream and one
                                 internal stream, forked and joined by events);
                                 1 = everything on the caller's stream             */
+    int32_t  dd_mode;        /* soar_dd_mode; dss_radius is ignored for BRACKET     */
 } soar_params;
 
-/* Fills *p with the hot-path defaults: SOAR, block 16, T = 1, K = 4, beta = {1}. */
+/* Fills *p with the single-step defaults: SOAR, block 16, T = 1, K = 4, beta = {1},
+ * window candidates. */
 void soar_default_params(soar_params *p);
+
+/* Fills *p with the full algorithm's settings of App. B.3: T = 15, 101 factors
+ * beta in [0.5, 1.5], the two enclosing E4M3 codes, early stop at 1e-3. */
+void soar_paper_params(soar_params *p);
 
 /*
  * Bytes of device workspace soar_quantize needs for a rows x cols tensor
@@ -109,6 +127,19 @@ size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *param
  * projection of Delta*, Appendix D) that minimises the block error of Eq. 8,
  * candidates being tried in the order 0,-1,+1,-2,+2,... and a later one winning
  * only if strictly better in binary32.
+ *
+ *
+ * The iterated path (taken when params differ from T = 1, beta = {1}, window
+ * candidates, or when a descriptor of soar_quantize_batch asks for the trace)
+ * runs Algorithm 1 as printed: in every iteration alpha <- Eq. 5 from the
+ * current codes and stored scales, Delta* <- Eq. 6, then for each factor beta in
+ * ascending order codes = Q_FP4(W / (alpha Delta* beta)) and, for each stored-
+ * scale candidate (window order as above, or lower code then upper code), the
+ * Eq. 8 error; the first pair with the smallest binary32 error is kept.  After
+ * each iteration the tensor's error (binary64 adjacent-pair tree over the block
+ * errors) is compared with the previous one for the early stop.  With T = 1,
+ * beta = {1} and window candidates both paths return the same bytes.
+ * search_mode does not apply to the iterated path (all pairs are evaluated).
  *
  * d_w            in   weights, bf16 or fp32 (see conventions)
  * d_codes        out  rows*cols/2 bytes
@@ -136,6 +167,11 @@ typedef struct {
     float      *d_global_scale;
     double     *d_sse;           /* may be NULL */
     int32_t    *d_status;        /* may be NULL */
+    int32_t    *d_iters_run;     /* may be NULL; 1 int32: iterations carried out (0 for an
+                                    all-zero or non-finite tensor)                      */
+    double     *d_sse_trace;     /* may be NULL; iters+1 doubles: [0] the error of the
+                                    Eq. 1-2 state, [t] the error after iteration t;
+                                    entries after an early stop are not written         */
 } soar_tensor_desc;
 
 /*
@@ -192,7 +228,8 @@ soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, v
  */
 typedef enum {
     SOAR_KERNEL_INIT = 0, SOAR_KERNEL_ABSMAX = 1, SOAR_KERNEL_STATS = 2, SOAR_KERNEL_SEARCH = 3,
-    SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_COUNT = 6
+    SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_ITER_INIT = 6, SOAR_KERNEL_ITER = 7,
+    SOAR_KERNEL_COUNT = 8
 } soar_kernel_id;
 void        soar_kernel_timing_enable(int enable);
 soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches);

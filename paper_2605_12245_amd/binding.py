@@ -19,11 +19,13 @@ SOAR_BF16, SOAR_FP32 = 0, 1
 SOAR_METHOD_RTN, SOAR_METHOD_SOAR = 0, 1
 SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
 SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO = 1, 2
+SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 (SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
- SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_COUNT) = range(7)
+ SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER,
+ SOAR_KERNEL_COUNT) = range(9)
 
 EXPORTS = (
-    "soar_default_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
+    "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
     "soar_quantize_batch",
     "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
@@ -47,6 +49,7 @@ class soar_params(C.Structure):
         ("iters", C.c_int32), ("dss_radius", C.c_int32), ("n_beta", C.c_int32),
         ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
         ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32), ("streams", C.c_int32),
+        ("dd_mode", C.c_int32),
     ]
 
 
@@ -56,6 +59,7 @@ class soar_tensor_desc(C.Structure):
         ("rows", C.c_int64), ("cols", C.c_int64), ("ld_elems", C.c_int64),
         ("d_codes", C.c_void_p), ("d_scales", C.c_void_p), ("d_global_scale", C.c_void_p),
         ("d_sse", C.c_void_p), ("d_status", C.c_void_p),
+        ("d_iters_run", C.c_void_p), ("d_sse_trace", C.c_void_p),
     ]
 
 
@@ -72,6 +76,8 @@ def lib():
     vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
     L.soar_default_params.argtypes = [C.POINTER(soar_params)]
     L.soar_default_params.restype = None
+    L.soar_paper_params.argtypes = [C.POINTER(soar_params)]
+    L.soar_paper_params.restype = None
     L.soar_workspace_bytes.argtypes = [i64, i64, C.POINTER(soar_params)]
     L.soar_workspace_bytes.restype = C.c_size_t
     L.soar_batch_workspace_bytes.argtypes = [i32, C.POINTER(soar_tensor_desc), C.POINTER(soar_params)]
@@ -111,6 +117,23 @@ def soar_default_params(method: int = SOAR_METHOD_SOAR, dss_radius: int = 4,
     p.method = method
     p.dss_radius = dss_radius
     p.search_mode = search_mode
+    p.tiles_per_wg = tiles_per_wg
+    p.streams = streams
+    return p
+
+
+def soar_paper_params(iters: Optional[int] = None, n_beta: Optional[int] = None,
+                      beta_lo: Optional[float] = None, beta_hi: Optional[float] = None,
+                      dd_mode: Optional[int] = None, dss_radius: Optional[int] = None,
+                      early_stop_rel: Optional[float] = None, tiles_per_wg: int = 0,
+                      streams: int = 0) -> soar_params:
+    """The full algorithm's settings; any argument given overrides one field."""
+    p = soar_params()
+    lib().soar_paper_params(C.byref(p))
+    for name, v in (("iters", iters), ("n_beta", n_beta), ("beta_lo", beta_lo), ("beta_hi", beta_hi),
+                    ("dd_mode", dd_mode), ("dss_radius", dss_radius), ("early_stop_rel", early_stop_rel)):
+        if v is not None:
+            setattr(p, name, v)
     p.tiles_per_wg = tiles_per_wg
     p.streams = streams
     return p
@@ -204,6 +227,8 @@ class Quantized:
     global_scale: torch.Tensor   # float32 [1]
     sse: torch.Tensor            # float64 [1]
     status: torch.Tensor         # int32 [1]
+    iters_run: Optional[torch.Tensor] = None   # int32 [1], iterated path
+    sse_trace: Optional[torch.Tensor] = None   # float64 [iters + 1], iterated path; NaN where not written
 
 
 def new_workspace(rows: int, cols: int, params: soar_params, device) -> torch.Tensor:
@@ -242,11 +267,39 @@ def quantize(w: torch.Tensor, method: int = SOAR_METHOD_SOAR, dss_radius: int = 
     return out
 
 
+def new_outputs(rows: int, cols: int, device, iters: int = 0) -> Quantized:
+    """Output buffers for one tensor; iters > 0 adds the iterated path's two extra outputs."""
+    q = Quantized(torch.empty((rows, cols // 2), dtype=torch.uint8, device=device),
+                  torch.empty((rows, cols // 16), dtype=torch.uint8, device=device),
+                  torch.empty(1, dtype=torch.float32, device=device),
+                  torch.empty(1, dtype=torch.float64, device=device),
+                  torch.empty(1, dtype=torch.int32, device=device))
+    if iters > 0:
+        q.iters_run = torch.zeros(1, dtype=torch.int32, device=device)
+        q.sse_trace = torch.full((iters + 1,), float("nan"), dtype=torch.float64, device=device)
+    return q
+
+
 def make_desc(w: torch.Tensor, out: Quantized) -> soar_tensor_desc:
     rows, cols, ld = _check_matrix(w)
     return soar_tensor_desc(w.data_ptr(), _dtype_code(w), rows, cols, ld, out.codes.data_ptr(),
                             out.scales.data_ptr(), out.global_scale.data_ptr(), out.sse.data_ptr(),
-                            out.status.data_ptr())
+                            out.status.data_ptr(),
+                            out.iters_run.data_ptr() if out.iters_run is not None else None,
+                            out.sse_trace.data_ptr() if out.sse_trace is not None else None)
+
+
+def quantize_iter(w: torch.Tensor, params: soar_params, workspace: Optional[torch.Tensor] = None,
+                  out: Optional[Quantized] = None) -> Quantized:
+    """One tensor through the iterated path (soar_quantize_batch with n = 1), with the error trace."""
+    rows, cols, _ = _check_matrix(w)
+    if out is None:
+        out = new_outputs(rows, cols, w.device, params.iters)
+    desc = make_desc(w, out)
+    if workspace is None:
+        workspace = new_batch_workspace([desc], params, w.device)
+    quantize_batch([desc], params, workspace)
+    return out
 
 
 def quantize_batch(descs: Sequence[soar_tensor_desc], params: soar_params, workspace: torch.Tensor) -> None:

@@ -9,6 +9,10 @@
 //            (Appendix D), Q1 = Q_FP4(W/(alpha1 Delta*)), search of the stored
 //            scale over centre-K..centre+K by Eq. 8, pack, error sum
 //
+// Algorithm 1 in full (T iterations, a grid of factors beta for the quantization
+// scale, early stop) runs as absmax, one pass that builds the Eq. 1-2 state, and
+// one arithmetic-bound pass per iteration; see k_iter.
+//
 // Work decomposition: one lane owns one 16-element block (two 128-bit loads for
 // bf16), so every per-block reduction is a register chain with no cross-lane
 // traffic.  A workgroup of 256 lanes owns "tiles" of 256 consecutive blocks.
@@ -44,6 +48,8 @@ constexpr int kSlots = 64;               // first-level arrival counters
 constexpr int kSlotStride = 32;          // in uint32: one counter per 128 bytes
 constexpr int kKernels = 3;              // absmax, stats, search
 constexpr int kLanes = 2;                // streams a batch is spread over
+constexpr int kMaxBeta = 4096;           // factors of the quantization-scale grid, at most
+constexpr int kMaxIters = 64;
 constexpr uint32_t kE4M3Min = 0x01u, kE4M3Max = 0x7Eu;
 
 // Control words of one tensor slot.  soar_quantize* zeroes them once per call;
@@ -53,8 +59,9 @@ struct Ctrl {
     uint32_t amax_bits;      // max |w| as binary32 bits
     float    alpha0;
     float    alpha1;
-    uint32_t pad;
+    uint32_t stopped;        // iterated path: the early stop has fired
     double   N, M;
+    double   prev_sse;       // iterated path: error before the iteration now running
 };
 constexpr size_t kCtrlBytes = 256;
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
@@ -84,7 +91,9 @@ struct Task {
     uint32_t *counters;      // [kKernels][kSlots] arrival counters, kSlotStride apart
     uint32_t *slot_max;      // [kSlots] partial maxima of the absmax kernel, kSlotStride apart
     double   *part;          // [3][kMaxPartials] partial sums N, M, error
-    float    *rho;           // [nblk] a / b of the Eq. 1-2 state, or -Delta0 where b == 0
+    float    *rho;           // [nblk] a / b of the current state, or -Delta^d where b == 0
+    int32_t  *iters_run;     // iterated path, may be null
+    double   *trace;         // iterated path, may be null: iters+1 errors
 };
 
 struct Batch {
@@ -92,6 +101,12 @@ struct Batch {
     uint32_t n;
     int32_t  radius;
     int32_t  full_search;
+    // iterated path
+    int32_t  iter_t;         // iteration this launch carries out
+    int32_t  n_beta;
+    int32_t  dd_mode;
+    float    beta_lo, beta_hi;
+    float    early_stop_rel;
 };
 
 typedef Task Geom;           // the addressing fields are all block_offset needs
@@ -724,6 +739,261 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     reset_counters(counters, &t.ctrl->top[2]);
 }
 
+// ------------------------------------------------------------------ iterated path
+// Sums of up to three per-block binary64 terms over the blocks of a workgroup, as the
+// adjacent-pair tree over the flat block index: wave tree, four waves, then a
+// binary-counter stack over the workgroup's consecutive tiles.  Call once per tile
+// (tile k of the workgroup, all lanes); after the last tile lane 0 holds the sums.
+template <int NS>
+struct TileTree {
+    double (*s_wave)[4];     // [NS][4]
+    double (*s_stack)[32];   // [NS][32]
+    double wg[NS] = {};
+    __device__ __forceinline__ void add_tile(uint32_t k, const double term[NS])
+    {
+        double v[NS];
+#pragma unroll
+        for (int n = 0; n < NS; ++n) v[n] = wave_pair_tree(term[n]);
+        __syncthreads();                                   // s_wave free again
+        if ((threadIdx.x & 63) == 0)
+#pragma unroll
+            for (int n = 0; n < NS; ++n) s_wave[n][threadIdx.x >> 6] = v[n];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                double x = (s_wave[n][0] + s_wave[n][1]) + (s_wave[n][2] + s_wave[n][3]);
+                uint32_t lvl = 0;
+                while ((k >> lvl) & 1u) { x = s_stack[n][lvl] + x; ++lvl; }
+                s_stack[n][lvl] = x;
+                wg[n] = x;
+            }
+        }
+    }
+};
+
+// largest E4M3 code in [0x01, 0x7E] whose value does not exceed y (0x01 if none does)
+__device__ __forceinline__ int e4m3_floor_code(float y)
+{
+    const int normal = (int)(__float_as_uint(y) >> 20) - (120 << 3);
+    const int sub = (int)(fminf(y, 1.0f) * 512.0f);
+    const int code = (y >= 0x1p-6f) ? normal : sub;
+    return min(max(code, (int)kE4M3Min), (int)kE4M3Max);
+}
+
+// The Eq. 1-2 state of Algorithm 1 (Delta^q = Delta^d = Delta0) for the iterated
+// path: per block the ratio a/b for Eq. 6 and the error of that state; per tensor
+// the sums of Eq. 5 (-> the global scale of iteration 0) and the error before any
+// iteration.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
+{
+    __shared__ double s_wave[3][4];
+    __shared__ double s_stack[3][32];
+    __shared__ double s_tree[kWG];
+    __shared__ uint32_t s_last;
+
+    uint32_t lwg;
+    const Task t = batch.t[find_task(batch, lwg)];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t amax_bits = t.ctrl->amax_bits;
+    const bool degenerate = amax_bits == 0u || amax_bits >= 0x7F800000u;
+    const float alpha0 = f_of(amax_bits) / 2688.0f;
+    const float alpha0_m = alpha0 * 6.0f;
+
+    TileTree<3> tree{s_wave, s_stack};
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        double term[3] = {0.0, 0.0, 0.0};
+        if (i < t.nblk) {
+            float rho = 0.0f;
+            if (!degenerate) {
+                float w[16], q[16];
+                uint32_t nib[2], c0;
+                float delta0, a, b;
+                load_block<DT>(t.w, block_offset(t, i), w);
+                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                block_sums(w, q, a, b);
+                term[0] = (double)a * (double)delta0;
+                term[1] = ((double)b * (double)delta0) * (double)delta0;
+                term[2] = (double)block_error(w, q, alpha0 * delta0);
+                rho = (b == 0.0f) ? -delta0 : a / b;
+            }
+            t.rho[i] = rho;
+        }
+        tree.add_tile(k, term);
+    }
+    uint32_t *counters = t.counters + 1 * kSlots * kSlotStride;
+    if (tid == 0) {
+        publish(t.part + lwg, tree.wg[0]);
+        publish(t.part + kMaxPartials + lwg, tree.wg[1]);
+        publish(t.part + 2 * kMaxPartials + lwg, tree.wg[2]);
+        s_last = arrive_is_last(counters, &t.ctrl->top[1], t.n_wg, lwg) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
+    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
+    const double E = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    if (tid == 0) {
+        t.ctrl->alpha0 = alpha0;
+        t.ctrl->alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;     // the global scale of iteration 0
+        t.ctrl->N = N;
+        t.ctrl->M = M;
+        t.ctrl->prev_sse = E;
+        t.ctrl->stopped = 0u;
+        if (!degenerate && t.trace) t.trace[0] = E;
+    }
+    reset_counters(counters, &t.ctrl->top[1]);
+}
+
+// One iteration of Algorithm 1.  On entry ctrl->alpha1 holds the Eq. 5 global
+// scale for the current codes and stored scales and rho[i] the block ratio a/b
+// (Eq. 6 is rho / alpha).  Per block: the joint search of Sec. 3.3 over
+// (factor beta ascending) x (stored-scale candidates in their order), keeping
+// the first pair with the smallest binary32 error; the block's codes, stored
+// scale, and -- because the codes of the winning pair ARE the codes the next
+// iteration starts from -- the next a/b and Eq. 5 terms.  Per tensor: the error
+// after this iteration (exact adjacent-pair tree, so that the early-stop test
+// is reproducible), the stop flag and the next global scale.
+// A tensor whose stop flag is set is skipped by every later launch.
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
+{
+    __shared__ double s_wave[3][4];
+    __shared__ double s_stack[3][32];
+    __shared__ double s_tree[kWG];
+    __shared__ float s_beta[kMaxBeta];
+    __shared__ uint32_t s_last;
+
+    uint32_t lwg;
+    const Task t = batch.t[find_task(batch, lwg)];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t amax_bits = t.ctrl->amax_bits;
+    const bool allzero = amax_bits == 0u;
+    const bool degenerate = allzero || amax_bits >= 0x7F800000u;
+    if (degenerate ? batch.iter_t != 0 : t.ctrl->stopped != 0u) return;     // uniform over the tensor's workgroups
+
+    const int n_beta = batch.n_beta;
+    for (int k = (int)tid; k < n_beta; k += kWG)
+        s_beta[k] = n_beta <= 1 ? batch.beta_lo
+                                : (batch.beta_lo * (float)(n_beta - 1 - k) + batch.beta_hi * (float)k) / (float)(n_beta - 1);
+    __syncthreads();
+
+    const float alpha = t.ctrl->alpha1;
+    const bool bracket = batch.dd_mode == SOAR_DD_BRACKET;
+    const int radius = batch.radius;
+
+    TileTree<3> tree{s_wave, s_stack};
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        double term[3] = {0.0, 0.0, 0.0};
+        if (i < t.nblk && amax_bits < 0x7F800000u) {
+            float w[16], q[16];
+            uint32_t best_nib[2] = {0u, 0u};
+            int best_code = (int)kE4M3Min;
+            float best_err = 0.0f;
+            load_block<DT>(t.w, block_offset(t, i), w);
+            if (allzero) {
+                float x[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) x[j] = w[j];
+                best_nib[0] = fp4x8(x);
+                best_nib[1] = fp4x8(x + 8);
+            } else {
+                const float rho = t.rho[i];
+                const float delta_star = (rho < 0.0f) ? -rho : rho / alpha;
+                bool have = false;
+                if (bracket) {
+                    const int lo = e4m3_floor_code(delta_star);
+                    const int hi = min(lo + 1, (int)kE4M3Max);           // hi == lo can never win
+                    const float s_lo = alpha * e4m3_value((uint32_t)lo);
+                    const float s_hi = alpha * e4m3_value((uint32_t)hi);
+                    for (int kb = 0; kb < n_beta; ++kb) {
+                        uint32_t nib[2];
+                        assign_codes(w, alpha * (delta_star * s_beta[kb]), nib, q);
+                        const float e_lo = block_error(w, q, s_lo);
+                        const float e_hi = block_error(w, q, s_hi);
+                        if (!have || e_lo < best_err) {
+                            have = true; best_err = e_lo; best_code = lo; best_nib[0] = nib[0]; best_nib[1] = nib[1];
+                        }
+                        if (e_hi < best_err) {
+                            best_err = e_hi; best_code = hi; best_nib[0] = nib[0]; best_nib[1] = nib[1];
+                        }
+                    }
+                } else {
+                    const int centre = (int)e4m3_project(delta_star);
+                    for (int kb = 0; kb < n_beta; ++kb) {
+                        uint32_t nib[2];
+                        assign_codes(w, alpha * (delta_star * s_beta[kb]), nib, q);
+                        // candidates centre, -1, +1, ...; a code clamped into [0x01, 0x7E] repeats an
+                        // earlier candidate of the same beta and can then never win
+                        for (int c = 0; c <= 2 * radius; ++c) {
+                            const int o = (c + 1) >> 1;
+                            const int code = (c & 1) ? max(centre - o, (int)kE4M3Min) : min(centre + o, (int)kE4M3Max);
+                            const float e = block_error(w, q, alpha * e4m3_value((uint32_t)code));
+                            if (!have || e < best_err) {
+                                have = true; best_err = e; best_code = code; best_nib[0] = nib[0]; best_nib[1] = nib[1];
+                            }
+                        }
+                    }
+                }
+                // the state the next iteration starts from
+                float a, b;
+                fp4x8_values(best_nib[0], q);
+                fp4x8_values(best_nib[1], q + 8);
+                block_sums(w, q, a, b);
+                const float d = e4m3_value((uint32_t)best_code);
+                term[0] = (double)a * (double)d;
+                term[1] = ((double)b * (double)d) * (double)d;
+                term[2] = (double)best_err;
+                t.rho[i] = (b == 0.0f) ? -d : a / b;
+            }
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            u32x2 packed = {best_nib[0], best_nib[1]};
+            reinterpret_cast<u32x2 *>(t.codes)[i] = packed;
+            t.scales[i] = (uint8_t)best_code;
+        }
+        tree.add_tile(k, term);
+    }
+    uint32_t *counters = t.counters + 2 * kSlots * kSlotStride;
+    if (tid == 0) {
+        publish(t.part + lwg, tree.wg[0]);
+        publish(t.part + kMaxPartials + lwg, tree.wg[1]);
+        publish(t.part + 2 * kMaxPartials + lwg, tree.wg[2]);
+        s_last = arrive_is_last(counters, &t.ctrl->top[2], t.n_wg, lwg) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
+    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
+    const double cur = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    if (tid == 0) {
+        if (degenerate) {
+            *t.gscale = allzero ? 1.0f : __builtin_nanf("");
+            if (t.sse) *t.sse = allzero ? 0.0 : __builtin_nan("");
+            if (t.status) *t.status = allzero ? SOAR_STATUS_ALLZERO : SOAR_STATUS_NONFINITE;
+            if (t.iters_run) *t.iters_run = 0;
+        } else {
+            const double prev = t.ctrl->prev_sse;
+            *t.gscale = alpha;
+            if (t.sse) *t.sse = cur;
+            if (t.status) *t.status = 0;
+            if (t.iters_run) *t.iters_run = batch.iter_t + 1;
+            if (t.trace) t.trace[batch.iter_t + 1] = cur;
+            const bool stop = batch.early_stop_rel > 0.0f && (prev - cur) < (double)batch.early_stop_rel * prev;
+            t.ctrl->stopped = stop ? 1u : 0u;
+            t.ctrl->prev_sse = cur;
+            t.ctrl->alpha1 = (M > 0.0) ? (float)(N / M) : alpha;      // Eq. 5 for the next iteration
+            t.ctrl->N = N;
+            t.ctrl->M = M;
+        }
+    }
+    reset_counters(counters, &t.ctrl->top[2]);
+}
+
 // Eq. 3
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
@@ -826,8 +1096,14 @@ bool valid_params(const soar_params *p)
 {
     if (!p || p->struct_size != sizeof(soar_params)) return false;
     if (p->method != SOAR_METHOD_RTN && p->method != SOAR_METHOD_SOAR) return false;
-    if (p->block != 16 || p->iters != 1 || p->n_beta != 1) return false;
-    if (p->beta_lo != 1.0f || p->beta_hi != 1.0f) return false;
+    if (p->block != 16) return false;
+    if (p->iters < 1 || p->iters > kMaxIters || p->n_beta < 1 || p->n_beta > kMaxBeta) return false;
+    if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo) || !(p->beta_hi < 1e30f)) return false;
+    if (!(p->early_stop_rel >= 0.0f) || !(p->early_stop_rel < 1e30f)) return false;
+    if (p->dd_mode != SOAR_DD_WINDOW && p->dd_mode != SOAR_DD_BRACKET) return false;
+    if (p->method == SOAR_METHOD_RTN &&
+        (p->iters != 1 || p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW))
+        return false;
     if (p->dss_radius < 0 || p->dss_radius > 125) return false;
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
@@ -850,6 +1126,12 @@ soar_status check_matrix_ptr(const void *p, int dtype, int64_t ld)
     if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return SOAR_ERR_ALIGN;
     if ((ld * es) % 16 != 0) return SOAR_ERR_ALIGN;
     return SOAR_OK;
+}
+
+// Algorithm 1 beyond the single-step settings
+bool iterated_params(const soar_params *p)
+{
+    return p->iters != 1 || p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW;
 }
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -984,6 +1266,30 @@ soar_status launch_group(const Batch &b, uint32_t total_wg, int method, hipStrea
     return SOAR_OK;
 }
 
+// absmax, the Eq. 1-2 state, then one launch per iteration; a tensor that has
+// stopped early (or is degenerate) makes its workgroups of the later launches return at once
+template <int DT>
+soar_status launch_group_iter(Batch &b, uint32_t total_wg, int iters, hipStream_t st)
+{
+    {
+        ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
+        hipLaunchKernelGGL(k_absmax<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        SOAR_LAUNCH_CHECK();
+    }
+    {
+        ScopedTimer t(SOAR_KERNEL_ITER_INIT, st);
+        hipLaunchKernelGGL(k_iter_init<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        SOAR_LAUNCH_CHECK();
+    }
+    for (int it = 0; it < iters; ++it) {
+        b.iter_t = it;
+        ScopedTimer t(SOAR_KERNEL_ITER, st);
+        hipLaunchKernelGGL(k_iter<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        SOAR_LAUNCH_CHECK();
+    }
+    return SOAR_OK;
+}
+
 soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params, void *d_workspace,
                       size_t workspace_bytes, hipStream_t st)
 {
@@ -995,6 +1301,10 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         soar_status s = validate_tensor(descs[k], params);
         if (s != SOAR_OK) return s;
     }
+    bool iterated = iterated_params(params);
+    for (int32_t k = 0; k < n; ++k) iterated = iterated || descs[k].d_iters_run || descs[k].d_sse_trace;
+    if (iterated && params->method != SOAR_METHOD_SOAR) return SOAR_ERR_PARAM;
+
     if (n == 0) return SOAR_OK;
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
     if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
@@ -1037,11 +1347,20 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         b.n = (uint32_t)(j - i);
         b.radius = params->dss_radius;
         b.full_search = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        b.n_beta = params->n_beta;
+        b.dd_mode = params->dd_mode;
+        b.beta_lo = params->beta_lo;
+        b.beta_hi = params->beta_hi;
+        b.early_stop_rel = params->early_stop_rel;
+        // the iterated kernels are arithmetic-bound: the smallest workgroups balance best
+        const uint32_t tpw = params->tiles_per_wg ? (uint32_t)params->tiles_per_wg : (iterated ? 1u : 0u);
         uint32_t wg = 0;
         char *per_block = lane_base + (size_t)kGroupMax * kSlotBytes;
         for (int32_t k = i; k < j; ++k) {
             const soar_tensor_desc &d = descs[k];
-            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, (uint32_t)params->tiles_per_wg);
+            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, tpw);
+            t.iters_run = d.d_iters_run;
+            t.trace = d.d_sse_trace;
             t.codes = d.d_codes;
             t.scales = d.d_scales;
             t.gscale = d.d_global_scale;
@@ -1058,8 +1377,12 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             per_block += align256((size_t)t.nblk * sizeof(float));
             b.t[k - i] = t;
         }
-        result = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, lane_stream[lane])
-                                             : launch_group<SOAR_FP32>(b, wg, params->method, lane_stream[lane]);
+        if (iterated)
+            result = descs[i].dtype == SOAR_BF16 ? launch_group_iter<SOAR_BF16>(b, wg, params->iters, lane_stream[lane])
+                                                 : launch_group_iter<SOAR_FP32>(b, wg, params->iters, lane_stream[lane]);
+        else
+            result = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, lane_stream[lane])
+                                                 : launch_group<SOAR_FP32>(b, wg, params->method, lane_stream[lane]);
         i = j;
     }
     if (lanes > 1) {
@@ -1093,6 +1416,20 @@ void soar_default_params(soar_params *p)
     p->search_mode = SOAR_SEARCH_AUTO;
     p->tiles_per_wg = 0;
     p->streams = 0;
+    p->dd_mode = SOAR_DD_WINDOW;
+}
+
+void soar_paper_params(soar_params *p)
+{
+    if (!p) return;
+    soar_default_params(p);
+    p->iters = 15;
+    p->n_beta = 101;
+    p->beta_lo = 0.5f;
+    p->beta_hi = 1.5f;
+    p->dd_mode = SOAR_DD_BRACKET;
+    p->dss_radius = 1;
+    p->early_stop_rel = 1e-3f;
 }
 
 size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *params)
@@ -1125,6 +1462,8 @@ soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64
     d.d_global_scale = d_global_scale;
     d.d_sse = d_sse;
     d.d_status = d_status;
+    d.d_iters_run = nullptr;
+    d.d_sse_trace = nullptr;
     return run_batch(1, &d, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -43,7 +43,13 @@ def test_default_params_and_workspace_query():
     assert B.soar_workspace_bytes(4096, 4090, p) == 0
     assert B.soar_workspace_bytes(0, 4096, p) == 0
     p.iters = 15
+    assert B.soar_workspace_bytes(4096, 4096, p) == n          # the iterated path needs no more
+    p.iters = 65
     assert B.soar_workspace_bytes(4096, 4096, p) == 0
+    q = B.soar_paper_params()
+    assert (q.iters, q.n_beta, q.dd_mode, q.method) == (15, 101, B.SOAR_DD_BRACKET, 1)
+    assert (q.beta_lo, q.beta_hi) == (0.5, 1.5) and abs(q.early_stop_rel - 1e-3) < 1e-9
+    assert B.soar_workspace_bytes(4096, 4096, q) == n
 
 
 def _q(p, d_w=0x1000, dtype=0, rows=64, cols=64, ld=64, codes=0x2000, scales=0x3000, gs=0x4000,
@@ -60,8 +66,10 @@ def test_host_side_argument_validation():
     assert _q(p, dtype=5) == 3
     assert _q(p, d_w=0x1008) == 7 and _q(p, ld=68) == 7 and _q(p, codes=0x2004) == 7
     assert _q(p, ws=0) == 5 and _q(p, ws=0x10010) == 5 and _q(p, ws_bytes=1000) == 5
-    for field, bad in (("method", 7), ("block", 32), ("iters", 2), ("dss_radius", -1), ("dss_radius", 200),
-                       ("n_beta", 101), ("beta_lo", 0.5), ("search_mode", 9), ("tiles_per_wg", 3), ("streams", 3),
+    for field, bad in (("method", 7), ("block", 32), ("iters", 0), ("iters", 65), ("dss_radius", -1),
+                       ("dss_radius", 200), ("n_beta", 0), ("n_beta", 4097), ("beta_lo", 0.0), ("beta_lo", 1.5),
+                       ("beta_hi", float("inf")), ("early_stop_rel", -1.0), ("early_stop_rel", float("nan")),
+                       ("dd_mode", 2), ("search_mode", 9), ("tiles_per_wg", 3), ("streams", 3),
                        ("struct_size", 4)):
         q = B.soar_default_params()
         setattr(q, field, bad)
@@ -71,6 +79,13 @@ def test_host_side_argument_validation():
     assert B.soar_recon_error(0x1000, 0, 4, 64, 64, 0x8, 0x10, 0x20, 0, 0) == 1
     assert B.soar_recon_error(0x1000, 3, 4, 64, 64, 0x8, 0x10, 0x20, 0x30, 0) == 3
     assert B.soar_e2m1_round_f32(0, 4, 0x10, 0) == 1 and B.soar_e4m3_project_f32(0x10, -1, 0x10, 0) == 2
+    # plain NVFP4 has no iterated form
+    for field, v in (("iters", 2), ("n_beta", 3), ("dd_mode", 1)):
+        q = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
+        setattr(q, field, v)
+        assert _q(q) == 4, field
+    d = B.soar_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0x4000, 0, 0, 0x5000, 0)
+    assert B.soar_quantize_batch([d], B.soar_default_params(B.SOAR_METHOD_RTN, 0), 0x10000, 1 << 20, 0) == 4
     d = B.soar_tensor_desc(0x1000, 0, 64, 60, 64, 0x2000, 0x3000, 0x4000, 0, 0)
     assert B.soar_quantize_batch([d], p, 0x10000, 1 << 20, 0) == 2
     assert B.soar_quantize_batch([], p, 0x10000, 1 << 20, 0) == 0
