@@ -29,6 +29,20 @@ BYTES_ABSMAX = 2.0
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
 # (profiles/config4_hbm_traffic_pmc.md): 2.2552 read + 0.5827 written.
 SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2552 + 0.5827
+# Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
+# method needs 16 products w*r, 16 roundings onto E2M1, 16 decoded values and, per stored-scale
+# candidate, 16 residuals (one fused op each) and 16 fused square-accumulates.
+VALU_PEAK_TFLOPS = 157.3       # MI355X FP32 vector, published (packed FP32)
+VALU_LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9   # one non-packed 32-bit op per lane: CUs x SIMDs x lanes/clk x clock
+
+
+def iter_flops_per_block_beta(ncand):
+    return 16 + 16 + 16 + ncand * (16 * 2 + 16 * 2)
+
+
+def iter_lane_ops_per_block_beta(ncand):
+    # the same work as machine operations: 16 mul, 8 two-element conversions each way, 32 fused ops per candidate
+    return 16 + 8 + 8 + ncand * 32
 
 
 def parse_args():
@@ -41,6 +55,11 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
+    ap.add_argument("--algorithm", choices=["single-step", "paper"], default="single-step",
+                    help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
+                         "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3")
+    ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
+    ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -84,7 +103,15 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
-    params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
+    paper = args.algorithm == "paper"
+    if paper:
+        params = B.soar_paper_params(iters=args.iters or None, early_stop_rel=0.0 if args.no_early_stop else None,
+                                     tiles_per_wg=args.tpw, streams=args.streams)
+        for o in outs:
+            o.iters_run = torch.zeros(1, dtype=torch.int32, device=dev)
+            o.sse_trace = torch.full((params.iters + 1,), float("nan"), dtype=torch.float64, device=dev)
+    else:
+        params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
     descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
     ws = B.new_batch_workspace(descs, params, dev)
 
@@ -114,7 +141,38 @@ def main():
     # launched on; same steps again, on one stream so that a kernel's duration is its own
     roofline = None
     kernels = {}
-    if not args.no_kernel_timing:
+    iters_run = [int(o.iters_run.item()) for o in outs] if paper else None
+    if paper and not args.no_kernel_timing:
+        n_prof = min(args.steps, 2)
+        p_one = B.soar_paper_params(iters=args.iters or None, early_stop_rel=0.0 if args.no_early_stop else None,
+                                    tiles_per_wg=args.tpw, streams=1)
+        B.soar_kernel_timing_enable(True)
+        for _ in range(n_prof):
+            B.quantize_batch(descs, p_one, ws)
+        torch.cuda.synchronize()
+        names = {B.SOAR_KERNEL_INIT: "init", B.SOAR_KERNEL_ABSMAX: "absmax",
+                 B.SOAR_KERNEL_ITER_INIT: "iter_init", B.SOAR_KERNEL_ITER: "iter"}
+        for kid, nm in names.items():
+            ms, n = B.soar_kernel_timing_read(kid)
+            kernels[nm] = {"launches": n, "total_ms": ms, "avg_us": (ms / n * 1e3) if n else None,
+                           "ms_per_step": ms / n_prof}
+        B.soar_kernel_timing_enable(False)
+        ncand = 2 if params.dd_mode == B.SOAR_DD_BRACKET else 2 * params.dss_radius + 1
+        block_iters = sum(it * (s.numel // 16) for it, s in zip(iters_run, specs))       # per step
+        flops = block_iters * params.n_beta * iter_flops_per_block_beta(ncand)
+        lane_ops = block_iters * params.n_beta * iter_lane_ops_per_block_beta(ncand)
+        t_iter = kernels["iter"]["ms_per_step"] * 1e-3
+        achieved = flops / t_iter / 1e12
+        roofline = {"kernel": "k_iter", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
+                    "lane_ops_per_s": lane_ops / t_iter, "lane_ops_peak_unpacked": VALU_LANE_OPS_PEAK,
+                    "frac_of_unpacked_issue_rate": lane_ops / t_iter / VALU_LANE_OPS_PEAK,
+                    "flops_per_block_beta": iter_flops_per_block_beta(ncand),
+                    "block_iterations_per_step": block_iters,
+                    "launches_per_step": kernels["iter"]["launches"] / n_prof,
+                    "note": "all k_iter launches of a step together (launches of tensors that have stopped "
+                            "return at once); HIP-event durations on the launch stream, single-stream pass"}
+    elif not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
         p_one = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, streams=1)
         B.soar_kernel_timing_enable(True)
@@ -144,7 +202,9 @@ def main():
 
     # ---- "MSE vs RTN": the plain max-based NVFP4 of Sec. 3.1 on the same tensors
     p_rtn = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
-    B.quantize_batch(descs, p_rtn, ws)
+    for o in outs:
+        o.iters_run = o.sse_trace = None       # plain descriptors: the single-step entry
+    B.quantize_batch([B.make_desc(w, o) for w, o in zip(weights, outs)], p_rtn, ws)
     torch.cuda.synchronize()
     sse_rtn = sum(float(o.sse.item()) for o in outs)
 
@@ -159,7 +219,16 @@ def main():
         host = [w.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) for w in weights[: len(sample)]]
         n_el = sum(s.numel for s in sample)
         t1 = time.perf_counter()
+        if paper:
+            sample, host = sample[:1], host[:1]
+            n_el = sample[0].numel
+            t1 = time.perf_counter()
+            oracle.quantize_iter(host[0], iters=params.iters, n_beta=params.n_beta, beta_lo=params.beta_lo,
+                                 beta_hi=params.beta_hi, dd_mode=params.dd_mode, dss_radius=params.dss_radius,
+                                 early_stop_rel=params.early_stop_rel)
         for s, h in zip(sample, host):
+            if paper:
+                break
             oracle.quantize(h, oracle.METHOD_SOAR, s.dss_radius)
         dt = time.perf_counter() - t1
         cpu = {"value": 2.0 * n_el / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(),
@@ -167,7 +236,7 @@ def main():
                "sample": f"first {len(sample)} tensor(s) of the workload ({n_el} weights), whole path"}
 
     out = {
-        "metric": "nvfp4_soar_quantize_throughput",
+        "metric": "nvfp4_soar_quantize_throughput" if not paper else "nvfp4_soar_full_algorithm_throughput",
         "value": gbs_in,
         "unit": "GB/s bf16 in",
         "n_gpus": 1,
@@ -181,7 +250,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
                    "dss_radius": K, "search": args.search, "entry_point": "soar_quantize_batch",
-                   "input": "bf16, resident in HBM"},
+                   "input": "bf16, resident in HBM", "algorithm": args.algorithm,
+                   **({"iters": params.iters, "n_beta": params.n_beta, "beta": [params.beta_lo, params.beta_hi],
+                       "dd_mode": "bracket" if params.dd_mode == B.SOAR_DD_BRACKET else "window",
+                       "early_stop_rel": params.early_stop_rel,
+                       "iterations_run_min_mean_max": [min(iters_run), sum(iters_run) / len(iters_run), max(iters_run)]}
+                      if paper else {})},
         "weights_per_s": E / (ms_per_step * 1e-3),
         "hbm_frac_3pass": BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "hbm_frac_single_touch": BYTES_SEARCH * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -220,13 +220,16 @@ __device__ __forceinline__ void assign_codes(const float w[16], float scale, uin
     fp4x8_values(nib[1], q + 8);
 }
 
-// Eq. 8 for one candidate scale s = alpha * d: ascending chain of fused operations
+// Eq. 8 for one candidate scale s = alpha * d: ascending chain of fused operations.
+// w - q*s is formed as fma(q, -s, w): the product's sign flips exactly, and negating the
+// one scale instead of the sixteen codes leaves nothing for the compiler to materialise.
 __device__ __forceinline__ float block_error(const float w[16], const float q[16], float s)
 {
+    const float ns = -s;
     float err = 0.0f;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-        float e = __builtin_fmaf(-q[j], s, w[j]);
+        float e = __builtin_fmaf(q[j], ns, w[j]);
         err = __builtin_fmaf(e, e, err);
     }
     return err;
@@ -781,6 +784,91 @@ __device__ __forceinline__ int e4m3_floor_code(float y)
     return min(max(code, (int)kE4M3Min), (int)kE4M3Max);
 }
 
+// 1 / s for s > 0 whose biased exponent lies in [1, 252]: the hardware estimate and one fused
+// Newton step.  Compared with the correctly rounded division on every binary32 pattern: identical
+// over that whole range (the patterns that differ are subnormal inputs and subnormal quotients).
+__device__ __forceinline__ float rcp_midrange(float s)
+{
+    const float y = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, y, 1.0f);
+    return __builtin_fmaf(e, y, y);
+}
+
+// assign_codes with the reciprocal chosen at compile time; nib carries the previous codes in
+// (every byte is overwritten) so that no register has to be cleared first
+template <bool FAST>
+__device__ __forceinline__ void assign_codes_rcp(const float w[16], float scale, uint32_t nib[2], float q[16])
+{
+    const float r = FAST ? rcp_midrange(scale) : 1.0f / scale;
+    float x[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = w[j] * r;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t v = nib[h];
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 0], x[8 * h + 1], 1.0f, 0);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 2], x[8 * h + 3], 1.0f, 1);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 4], x[8 * h + 5], 1.0f, 2);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 6], x[8 * h + 7], 1.0f, 3);
+        nib[h] = v;
+    }
+    fp4x8_values(nib[0], q);
+    fp4x8_values(nib[1], q + 8);
+}
+
+// The joint search of Sec. 3.3 for one block: factors beta ascending, for each the stored-scale
+// candidates in their order (bracket: c0 then c0+1; window: c0, -1, +1, ...), the first pair with
+// the smallest binary32 error wins.  Only the error and the winning factor are tracked in the
+// loop; the winner's codes are formed once more at the end.
+template <bool FAST>
+__device__ __forceinline__ void joint_search(const float w[16], float alpha, float delta_star, const float *s_beta,
+                                             int n_beta, bool bracket, int c0, int radius, float &best_err,
+                                             int &best_code, uint32_t best_nib[2], float q[16])
+{
+    uint32_t nib[2] = {0u, 0u};
+    float best = __builtin_inff();           // an error is never NaN; "first wins" for an infinite one too
+    float best_beta = s_beta[0];
+    if (bracket) {
+        const int lo = c0;
+        const int hi = min(lo + 1, (int)kE4M3Max);           // hi == lo can never win
+        const float s_lo = alpha * e4m3_value((uint32_t)lo);
+        const float s_hi = alpha * e4m3_value((uint32_t)hi);
+#pragma unroll 4
+        for (int kb = 0; kb < n_beta; ++kb) {
+            const float bk = s_beta[kb];
+            assign_codes_rcp<FAST>(w, alpha * (delta_star * bk), nib, q);
+            const float e_lo = block_error(w, q, s_lo);
+            const float e_hi = block_error(w, q, s_hi);
+            const float m = fminf(fminf(best, e_lo), e_hi);
+            best_beta = (m < best) ? bk : best_beta;         // strictly better only: the first factor keeps a tie
+            best = m;
+        }
+        // the winning factor once more: its codes, and which of the two stored scales it won with
+        assign_codes_rcp<FAST>(w, alpha * (delta_star * best_beta), best_nib, q);
+        const float e_lo = block_error(w, q, s_lo);
+        const float e_hi = block_error(w, q, s_hi);
+        const bool upper = e_hi < e_lo;                      // the lower code comes first and keeps a tie
+        best_code = upper ? hi : lo;
+        best_err = upper ? e_hi : e_lo;
+    } else {
+        best_code = c0;
+        for (int kb = 0; kb < n_beta; ++kb) {
+            const float bk = s_beta[kb];
+            assign_codes_rcp<FAST>(w, alpha * (delta_star * bk), nib, q);
+            // a code clamped into [0x01, 0x7E] repeats an earlier candidate of the same factor
+            // and can then never win
+            for (int c = 0; c <= 2 * radius; ++c) {
+                const int o = (c + 1) >> 1;
+                const int code = (c & 1) ? max(c0 - o, (int)kE4M3Min) : min(c0 + o, (int)kE4M3Max);
+                const float e = block_error(w, q, alpha * e4m3_value((uint32_t)code));
+                if (e < best) { best = e; best_beta = bk; best_code = code; }
+            }
+        }
+        best_err = best;
+        assign_codes_rcp<FAST>(w, alpha * (delta_star * best_beta), best_nib, q);
+    }
+}
+
 // The Eq. 1-2 state of Algorithm 1 (Delta^q = Delta^d = Delta0) for the iterated
 // path: per block the ratio a/b for Eq. 6 and the error of that state; per tensor
 // the sums of Eq. 5 (-> the global scale of iteration 0) and the error before any
@@ -905,45 +993,19 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
             } else {
                 const float rho = t.rho[i];
                 const float delta_star = (rho < 0.0f) ? -rho : rho / alpha;
-                bool have = false;
-                if (bracket) {
-                    const int lo = e4m3_floor_code(delta_star);
-                    const int hi = min(lo + 1, (int)kE4M3Max);           // hi == lo can never win
-                    const float s_lo = alpha * e4m3_value((uint32_t)lo);
-                    const float s_hi = alpha * e4m3_value((uint32_t)hi);
-                    for (int kb = 0; kb < n_beta; ++kb) {
-                        uint32_t nib[2];
-                        assign_codes(w, alpha * (delta_star * s_beta[kb]), nib, q);
-                        const float e_lo = block_error(w, q, s_lo);
-                        const float e_hi = block_error(w, q, s_hi);
-                        if (!have || e_lo < best_err) {
-                            have = true; best_err = e_lo; best_code = lo; best_nib[0] = nib[0]; best_nib[1] = nib[1];
-                        }
-                        if (e_hi < best_err) {
-                            best_err = e_hi; best_code = hi; best_nib[0] = nib[0]; best_nib[1] = nib[1];
-                        }
-                    }
-                } else {
-                    const int centre = (int)e4m3_project(delta_star);
-                    for (int kb = 0; kb < n_beta; ++kb) {
-                        uint32_t nib[2];
-                        assign_codes(w, alpha * (delta_star * s_beta[kb]), nib, q);
-                        // candidates centre, -1, +1, ...; a code clamped into [0x01, 0x7E] repeats an
-                        // earlier candidate of the same beta and can then never win
-                        for (int c = 0; c <= 2 * radius; ++c) {
-                            const int o = (c + 1) >> 1;
-                            const int code = (c & 1) ? max(centre - o, (int)kE4M3Min) : min(centre + o, (int)kE4M3Max);
-                            const float e = block_error(w, q, alpha * e4m3_value((uint32_t)code));
-                            if (!have || e < best_err) {
-                                have = true; best_err = e; best_code = code; best_nib[0] = nib[0]; best_nib[1] = nib[1];
-                            }
-                        }
-                    }
-                }
+                const int c0 = bracket ? e4m3_floor_code(delta_star) : (int)e4m3_project(delta_star);
+                // the reciprocal shortcut holds while the biased exponent of the scale stays in [1, 252];
+                // the scales of a block lie between those of the first and the last factor (to within
+                // rounding of the grid), which are asked to keep one binade of distance from both ends
+                const float s_first = alpha * (delta_star * s_beta[0]);
+                const float s_final = alpha * (delta_star * s_beta[n_beta - 1]);
+                const bool mid = ((__float_as_uint(s_first) >> 23) - 2u) < 250u && ((__float_as_uint(s_final) >> 23) - 2u) < 250u;
+                if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
+                    joint_search<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code, best_nib, q);
+                else
+                    joint_search<false>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code, best_nib, q);
                 // the state the next iteration starts from
                 float a, b;
-                fp4x8_values(best_nib[0], q);
-                fp4x8_values(best_nib[1], q + 8);
                 block_sums(w, q, a, b);
                 const float d = e4m3_value((uint32_t)best_code);
                 term[0] = (double)a * (double)d;
