@@ -220,6 +220,15 @@ soar_status soar_e2m1_round_f32(const float *d_x, int64_t n, uint8_t *d_out, voi
 soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream);
 
 /*
+ * The reciprocal used inside the iterated path's search loop (hardware estimate
+ * plus one fused Newton step), exposed so that the claim it rests on can be
+ * checked exhaustively: for every positive binary32 x whose biased exponent lies
+ * in [1, 252] the result is bit-identical to the correctly rounded 1/x.  (The
+ * kernel falls back to the division outside that range.)  d_x, d_out: n floats.
+ */
+soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, void *hip_stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the library
  * launches is bracketed by HIP events on its stream.  soar_kernel_timing_read
  * synchronises, returns total milliseconds and launch count of one kernel

@@ -28,6 +28,7 @@ EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
     "soar_quantize_batch",
     "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
+    "soar_rcp_midrange_f32",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
 )
 
@@ -96,6 +97,8 @@ def lib():
     L.soar_e2m1_round_f32.restype = i32
     L.soar_e4m3_project_f32.argtypes = [vp, i64, vp, vp]
     L.soar_e4m3_project_f32.restype = i32
+    L.soar_rcp_midrange_f32.argtypes = [vp, i64, vp, vp]
+    L.soar_rcp_midrange_f32.restype = i32
     L.soar_kernel_timing_enable.argtypes = [C.c_int]
     L.soar_kernel_timing_enable.restype = None
     L.soar_kernel_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -181,6 +184,10 @@ def soar_e2m1_round_f32(d_x, n, d_out, hip_stream) -> int:
 
 def soar_e4m3_project_f32(d_x, n, d_out, hip_stream) -> int:
     return int(lib().soar_e4m3_project_f32(d_x, n, d_out, hip_stream))
+
+
+def soar_rcp_midrange_f32(d_x, n, d_out, hip_stream) -> int:
+    return int(lib().soar_rcp_midrange_f32(d_x, n, d_out, hip_stream))
 
 
 def soar_kernel_timing_enable(enable: bool) -> None:

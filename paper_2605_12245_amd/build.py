@@ -1,4 +1,5 @@
-"""Build the HIP library (gfx950) into paper_2605_12245_amd/libsoar_hip.so."""
+"""Build the HIP library (gfx950) into paper_2605_12245_amd/libsoar_hip.so, and the
+stand-alone instruction-cost probe into paper_2605_12245_amd/valu_probe."""
 import os
 import subprocess
 import sys
@@ -7,6 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "soar_hip.hip")
 OUT = os.path.join(HERE, "libsoar_hip.so")
+PROBE_SRC = os.path.join(HERE, "csrc", "valu_probe.hip")
+PROBE_OUT = os.path.join(HERE, "valu_probe")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -ffp-contract=off: the kernels state every fused multiply-add explicitly; the
@@ -32,6 +35,14 @@ def build(verbose: bool = False, extra=()) -> str:
         print("\n".join(lines))
     if r.returncode != 0:
         raise RuntimeError("hipcc failed")
+    # the probe holds no arithmetic of the method: plain -O3, hand-written instruction streams
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", PROBE_SRC, "-o", PROBE_OUT]
+    if verbose:
+        print(" ".join(cmd))
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        print(r.stdout)
+        raise RuntimeError("hipcc failed (valu_probe)")
     return OUT
 
 

@@ -1129,6 +1129,12 @@ __global__ void k_e4m3_project(const float *x, int64_t n, uint8_t *out)
     if (i < n) out[i] = (uint8_t)e4m3_project(x[i]);
 }
 
+__global__ void k_rcp_midrange(const float *x, int64_t n, float *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = rcp_midrange(x[i]);
+}
+
 // ------------------------------------------------------------------ host side
 struct Timing {
     bool enabled = false;
@@ -1601,6 +1607,17 @@ soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, v
     if (n < 0 || n > ((int64_t)1 << 38)) return SOAR_ERR_SHAPE;
     if (n == 0) return SOAR_OK;
     hipLaunchKernelGGL(k_e4m3_project, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), d_x, n, d_out);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, void *hip_stream)
+{
+    if (!d_x || !d_out) return SOAR_ERR_NULL;
+    if (n < 0 || n > ((int64_t)1 << 38)) return SOAR_ERR_SHAPE;
+    if (n == 0) return SOAR_OK;
+    hipLaunchKernelGGL(k_rcp_midrange, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), d_x, n, d_out);
     SOAR_LAUNCH_CHECK();
     return SOAR_OK;

@@ -60,6 +60,22 @@ def run_one(w, p, what):
     return out, ref
 
 
+def test_loop_reciprocal_equals_the_division_on_its_whole_range():
+    """Every positive binary32 with biased exponent 1..252: estimate + one fused Newton step == 1/x."""
+    chunk = 1 << 26
+    out = torch.empty(chunk, dtype=torch.float32, device=DEV)
+    base = torch.arange(chunk, dtype=torch.int64, device=DEV)
+    one = np.float32(1.0)
+    for c in range(1 << 23, 253 << 23, chunk):
+        x = (base + c).to(torch.int32).view(torch.float32)
+        assert B.soar_rcp_midrange_f32(x.data_ptr(), chunk, out.data_ptr(), 0) == 0
+        got = out.cpu().numpy().view(np.uint32)
+        xh = (np.arange(chunk, dtype=np.uint32) + np.uint32(c)).view(np.float32)
+        want = (one / xh).view(np.uint32)
+        bad = got != want
+        assert not bad.any(), f"chunk {c:#x}: {np.count_nonzero(bad)} mismatches, first at {xh[bad][:4]}"
+
+
 def test_single_step_settings_match_the_single_step_path():
     """T = 1, beta = {1}, window: the iterated kernels return the bytes of the three-pass path."""
     for workload, div in ((1, 1), (2, 4)):
