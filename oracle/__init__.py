@@ -18,7 +18,7 @@ import numpy as np
 
 BF16, FP32 = 0, 1
 METHOD_RTN, METHOD_SOAR = 0, 1
-STATUS_NONFINITE, STATUS_ALLZERO = 1, 2
+STATUS_NONFINITE, STATUS_ALLZERO, STATUS_BAD_AMAX = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # SOAR_ORACLE_LIB lets the mutation test point the pins at a deliberately broken build
@@ -73,6 +73,10 @@ def lib():
             C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.POINTER(_IterParams),
             C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double),
             C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_void_p]
+        L.soar_oracle_quantize_rtn_amax.restype = C.c_int
+        L.soar_oracle_quantize_rtn_amax.argtypes = [
+            C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_float,
+            C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         L.soar_oracle_dequantize.restype = C.c_int
         L.soar_oracle_dequantize.argtypes = [
             C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
@@ -199,6 +203,22 @@ def quantize(w: np.ndarray, method: int = METHOD_SOAR, dss_radius: int = 4,
         trace = dict(bufs)
         trace.update(alpha0=np.float32(tr.alpha0), alpha1=np.float32(tr.alpha1), N=tr.N, M=tr.M)
     return Quantized(codes, scales, np.float32(g.value), float(sse.value), int(st.value), trace)
+
+
+def quantize_rtn_amax(w: np.ndarray, amax: float) -> Quantized:
+    """Max-based NVFP4 (Sec. 3.1) with a supplied tensor maximum."""
+    rows, cols, ld = _check2d(w)
+    codes = np.zeros((rows, cols // 2), dtype=np.uint8)
+    scales = np.zeros((rows, cols // 16), dtype=np.uint8)
+    g = C.c_float(0.0)
+    sse = C.c_double(0.0)
+    st = C.c_int32(0)
+    rc = lib().soar_oracle_quantize_rtn_amax(w.ctypes.data, _dtype_of(w), rows, cols, ld, C.c_float(amax),
+                                             codes.ctypes.data, scales.ctypes.data, C.byref(g), C.byref(sse),
+                                             C.byref(st))
+    if rc != 0:
+        raise ValueError("soar_oracle_quantize_rtn_amax: bad argument")
+    return Quantized(codes, scales, np.float32(g.value), float(sse.value), int(st.value), None)
 
 
 DD_WINDOW, DD_BRACKET = 0, 1

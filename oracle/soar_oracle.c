@@ -50,7 +50,7 @@
 
 enum { ORACLE_BF16 = 0, ORACLE_FP32 = 1 };
 enum { ORACLE_METHOD_RTN = 0, ORACLE_METHOD_SOAR = 1 };
-enum { ORACLE_STATUS_NONFINITE = 1, ORACLE_STATUS_ALLZERO = 2 };
+enum { ORACLE_STATUS_NONFINITE = 1, ORACLE_STATUS_ALLZERO = 2, ORACLE_STATUS_BAD_AMAX = 4 };
 
 /* ------------------------------------------------------------------------- */
 /* Number formats (Sec. 3.1)                                                  */
@@ -661,6 +661,58 @@ int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t co
     if (status) *status = 0;
     if (iters_run) *iters_run = done;
     free(dq); free(dd); free(a_all); free(b_all); free(termN); free(termM); free(errs);
+    return 0;
+}
+
+/*
+ * soar_oracle_quantize_rtn_amax -- the max-based NVFP4 of Sec. 3.1 (Eq. 1-2) with
+ * the tensor's maximum magnitude SUPPLIED instead of measured: the form in which
+ * the standard format is applied to activations (Appendix B.2), where the
+ * maximum comes from calibration or from an earlier pass.
+ *     alpha   = amax / (M_FP4 * M_FP8)
+ *     Delta_i = Q_E4M3( max|W_i| / (alpha * M_FP4) )      (clipped to 448)
+ *     codes   = Q_FP4( W_i / (alpha Delta_i) )              (saturating at +-6)
+ * so values above amax saturate.  amax must be finite and > 0; otherwise
+ * *status = ORACLE_STATUS_BAD_AMAX and nothing else is written.  The weights
+ * are not scanned for non-finite values in this mode (status stays 0).
+ */
+int soar_oracle_quantize_rtn_amax(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                                  float amax, uint8_t *codes, uint8_t *scales, float *global_scale,
+                                  double *sse, int32_t *status)
+{
+    if (!w || !codes || !scales || !global_scale) return -1;
+    if (rows <= 0 || cols <= 0 || cols % BLOCK != 0 || ld < cols) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32) return -1;
+    if (!isfinite(amax) || !(amax > 0.0f)) {
+        if (status) *status = ORACLE_STATUS_BAD_AMAX;
+        return 0;
+    }
+    const int64_t bpr = cols / BLOCK;
+    const int64_t nblk = rows * bpr;
+    const float alpha = amax / (M_FP4 * M_FP8);
+    const float alpha_m = alpha * M_FP4;
+    double *errs = (double *)malloc(sizeof(double) * (size_t)nblk);
+    if (!errs) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < nblk; ++i) {
+        int64_t r = i / bpr, cb = i % bpr;
+        float wv[BLOCK], q[BLOCK];
+        float bmax = 0.0f;
+        for (int j = 0; j < BLOCK; ++j) {
+            wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
+            if (fabsf(wv[j]) > bmax) bmax = fabsf(wv[j]);
+        }
+        uint8_t c = soar_oracle_e4m3_project(bmax / alpha_m);
+        float delta = soar_oracle_e4m3_value(c);
+        assign_codes(wv, alpha, delta, q);
+        scales[i] = c;
+        pack_block(wv, q, codes + i * (BLOCK / 2));
+        errs[i] = (double)block_error(wv, q, alpha * delta);
+    }
+    *global_scale = alpha;
+    if (sse) *sse = tree_sum(errs, nblk);
+    if (status) *status = 0;
+    free(errs);
     return 0;
 }
 

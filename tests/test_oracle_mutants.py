@@ -63,6 +63,14 @@ MUTANTS += [
     ("iter: trace entry of the wrong iteration", "if (sse_trace) sse_trace[t + 1] = cur;", "if (sse_trace) sse_trace[t + 1] = prev;"),
 ]
 
+# mistakes in the supplied-maximum form (caught by tests/test_oracle_rtn_amax.py)
+MUTANTS += [
+    ("amax: global scale without M_FP4", "const float alpha = amax / (M_FP4 * M_FP8);", "const float alpha = amax / M_FP8;"),
+    ("amax: block scale without M_FP4", "uint8_t c = soar_oracle_e4m3_project(bmax / alpha_m);", "uint8_t c = soar_oracle_e4m3_project(bmax / alpha);"),
+    ("amax: block scale from the supplied maximum", "uint8_t c = soar_oracle_e4m3_project(bmax / alpha_m);", "uint8_t c = soar_oracle_e4m3_project(amax / alpha_m);"),
+    ("amax: zero maximum accepted", "if (!isfinite(amax) || !(amax > 0.0f)) {", "if (!isfinite(amax)) {"),
+]
+
 
 @pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0].replace(" ", "_") for m in MUTANTS])
 def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
@@ -74,7 +82,12 @@ def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
     subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-w",
                     str(c_file), "-o", str(so_file), "-lm"], check=True)
     env = dict(os.environ, SOAR_ORACLE_LIB=str(so_file))
-    files = ["test_oracle_iter.py"] if name.startswith("iter:") else ["test_oracle_formats.py", "test_oracle_method.py"]
+    if name.startswith("iter:"):
+        files = ["test_oracle_iter.py"]
+    elif name.startswith("amax:"):
+        files = ["test_oracle_rtn_amax.py"]
+    else:
+        files = ["test_oracle_formats.py", "test_oracle_method.py"]
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"]
                        + [os.path.join(ROOT, "tests", f) for f in files],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
