@@ -57,7 +57,7 @@ MUTANTS += [
     ("iter: early stop compares with the first error", "        prev = cur;\n    }\n    memcpy(scales, dd", "    }\n    memcpy(scales, dd"),
     ("iter: global scale not advanced", "        alpha = alpha_new;\n        cur = tree_sum(errs, nblk);", "        cur = tree_sum(errs, nblk);"),
     ("iter: Eq. 6 with the previous global scale", "delta_star = (a_all[i] / b_all[i]) / alpha_new;", "delta_star = (a_all[i] / b_all[i]) / alpha;"),
-    ("iter: initial global scale without M_FP4", "float alpha = amax / (M_FP4 * M_FP8);", "float alpha = amax / M_FP8;"),
+    ("iter: initial global scale without M_FP4", "    float alpha = amax / (M_FP4 * M_FP8);\n    const float alpha0_m", "    float alpha = amax / M_FP8;\n    const float alpha0_m"),
     ("iter: initial block scale without M_FP4", "dd[i] = soar_oracle_e4m3_project(bmax / alpha0_m);", "dd[i] = soar_oracle_e4m3_project(bmax / alpha);"),
     ("iter: window searched upwards only", "++k)\n                    for (int sgn = -1; sgn <= 1; sgn += 2) {", "++k)\n                    for (int sgn = 1; sgn <= 1; sgn += 2) {"),
     ("iter: trace entry of the wrong iteration", "if (sse_trace) sse_trace[t + 1] = cur;", "if (sse_trace) sse_trace[t + 1] = prev;"),
