@@ -29,6 +29,8 @@ BYTES_ABSMAX = 2.0
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
 # (profiles/config4_hbm_traffic_pmc.md): 2.2552 read + 0.5827 written.
 SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2552 + 0.5827
+# the same for the one-pass plain NVFP4 with a supplied maximum (profiles/config4_rtn_amax.md)
+RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0201 + 0.5795
 # Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
 # method needs 16 products w*r, 16 roundings onto E2M1, 16 decoded values and, per stored-scale
 # candidate, 16 residuals (one fused op each) and 16 fused square-accumulates.
@@ -55,9 +57,10 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
-    ap.add_argument("--algorithm", choices=["single-step", "paper"], default="single-step",
+    ap.add_argument("--algorithm", choices=["single-step", "paper", "rtn-amax"], default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
-                         "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3")
+                         "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
+                         "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass)")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -104,7 +107,13 @@ def main():
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
     paper = args.algorithm == "paper"
-    if paper:
+    rtn_amax = args.algorithm == "rtn-amax"
+    amax_in = [None] * len(specs)
+    if rtn_amax:
+        # the supplied maxima: measured here, outside the timed region, as a calibration pass would
+        amax_in = [w.abs().max().float().reshape(1) for w in weights]
+        params = B.soar_default_params(B.SOAR_METHOD_RTN, 0, mode, args.tpw, args.streams)
+    elif paper:
         params = B.soar_paper_params(iters=args.iters or None, early_stop_rel=0.0 if args.no_early_stop else None,
                                      tiles_per_wg=args.tpw, streams=args.streams)
         for o in outs:
@@ -112,7 +121,7 @@ def main():
             o.sse_trace = torch.full((params.iters + 1,), float("nan"), dtype=torch.float64, device=dev)
     else:
         params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
-    descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+    descs = [B.make_desc(w, o, a) for w, o, a in zip(weights, outs, amax_in)]
     ws = B.new_batch_workspace(descs, params, dev)
 
     def step():
@@ -174,7 +183,8 @@ def main():
                             "return at once); HIP-event durations on the launch stream, single-stream pass"}
     elif not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
-        p_one = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, streams=1)
+        p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,
+                                      mode, args.tpw, streams=1)
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
             B.quantize_batch(descs, p_one, ws)
@@ -189,10 +199,14 @@ def main():
                            "GBps": (per_elem[nm] * E * n_prof / (ms * 1e-3) / 1e9) if ms > 0 and per_elem[nm] else None}
         B.soar_kernel_timing_enable(False)
         dom = max(("absmax", "stats", "search"), key=lambda k: kernels[k]["total_ms"])
+        if rtn_amax:
+            kernels = {k: v for k, v in kernels.items() if v["launches"]}
         achieved = kernels[dom]["GBps"]
         traffic = None
-        if dom == "search" and args.workload == 4 and not args.layers:
+        if dom == "search" and args.workload == 4 and not args.layers and not rtn_amax:
             traffic = SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
+        if rtn_amax and args.workload == 4 and not args.layers and RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4:
+            traffic = RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
         roofline = {"kernel": "k_" + dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                     "algorithmic_bytes_per_weight": per_elem[dom],
@@ -229,6 +243,9 @@ def main():
         for s, h in zip(sample, host):
             if paper:
                 break
+            if rtn_amax:
+                oracle.quantize_rtn_amax(h, float(amax_in[0].item()))
+                continue
             oracle.quantize(h, oracle.METHOD_SOAR, s.dss_radius)
         dt = time.perf_counter() - t1
         cpu = {"value": 2.0 * n_el / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(),
@@ -236,7 +253,8 @@ def main():
                "sample": f"first {len(sample)} tensor(s) of the workload ({n_el} weights), whole path"}
 
     out = {
-        "metric": "nvfp4_soar_quantize_throughput" if not paper else "nvfp4_soar_full_algorithm_throughput",
+        "metric": {"single-step": "nvfp4_soar_quantize_throughput", "paper": "nvfp4_soar_full_algorithm_throughput",
+                   "rtn-amax": "nvfp4_rtn_supplied_amax_throughput"}[args.algorithm],
         "value": gbs_in,
         "unit": "GB/s bf16 in",
         "n_gpus": 1,
@@ -257,7 +275,7 @@ def main():
                        "iterations_run_min_mean_max": [min(iters_run), sum(iters_run) / len(iters_run), max(iters_run)]}
                       if paper else {})},
         "weights_per_s": E / (ms_per_step * 1e-3),
-        "hbm_frac_3pass": BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "hbm_frac_3pass": (BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS) if not rtn_amax else None,
         "hbm_frac_single_touch": BYTES_SEARCH * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mse_vs_rtn": sse_soar / sse_rtn if sse_rtn > 0 else None,
         "sse_soar": sse_soar, "sse_rtn": sse_rtn,

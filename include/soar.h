@@ -70,6 +70,8 @@ typedef enum {
 /* data-dependent status bits written to *d_status */
 #define SOAR_STATUS_NONFINITE 1   /* NaN or Inf in the weights: outputs unspecified  */
 #define SOAR_STATUS_ALLZERO   2   /* every weight is zero                            */
+#define SOAR_STATUS_BAD_AMAX  4   /* supplied maximum not finite or not > 0: outputs
+                                     unspecified                                     */
 
 typedef struct {
     uint32_t struct_size;    /* sizeof(soar_params), for forward compatibility      */
@@ -172,6 +174,15 @@ typedef struct {
     double     *d_sse_trace;     /* may be NULL; iters+1 doubles: [0] the error of the
                                     Eq. 1-2 state, [t] the error after iteration t;
                                     entries after an early stop are not written         */
+    const float *d_amax_in;      /* may be NULL; method RTN only, and then for all tensors
+                                    of a batch or for none: 1 float, the tensor's maximum
+                                    magnitude SUPPLIED (activation quantization, Appendix
+                                    B.2: calibrated, or from an earlier pass) instead of
+                                    measured.  The tensor is then read once: alpha =
+                                    amax/(6*448), block scales clipped to 448, values above
+                                    amax saturate at +-6.  Not finite or not > 0:
+                                    SOAR_STATUS_BAD_AMAX.  The weights are not scanned for
+                                    non-finite values in this mode.                      */
 } soar_tensor_desc;
 
 /*

@@ -18,7 +18,7 @@ SOAR_OK = 0
 SOAR_BF16, SOAR_FP32 = 0, 1
 SOAR_METHOD_RTN, SOAR_METHOD_SOAR = 0, 1
 SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
-SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO = 1, 2
+SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX = 1, 2, 4
 SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 (SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
  SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER,
@@ -60,7 +60,7 @@ class soar_tensor_desc(C.Structure):
         ("rows", C.c_int64), ("cols", C.c_int64), ("ld_elems", C.c_int64),
         ("d_codes", C.c_void_p), ("d_scales", C.c_void_p), ("d_global_scale", C.c_void_p),
         ("d_sse", C.c_void_p), ("d_status", C.c_void_p),
-        ("d_iters_run", C.c_void_p), ("d_sse_trace", C.c_void_p),
+        ("d_iters_run", C.c_void_p), ("d_sse_trace", C.c_void_p), ("d_amax_in", C.c_void_p),
     ]
 
 
@@ -287,13 +287,15 @@ def new_outputs(rows: int, cols: int, device, iters: int = 0) -> Quantized:
     return q
 
 
-def make_desc(w: torch.Tensor, out: Quantized) -> soar_tensor_desc:
+def make_desc(w: torch.Tensor, out: Quantized, amax_in: Optional[torch.Tensor] = None) -> soar_tensor_desc:
+    """amax_in: float32 [1] on the GPU, the supplied tensor maximum (plain NVFP4 only)."""
     rows, cols, ld = _check_matrix(w)
     return soar_tensor_desc(w.data_ptr(), _dtype_code(w), rows, cols, ld, out.codes.data_ptr(),
                             out.scales.data_ptr(), out.global_scale.data_ptr(), out.sse.data_ptr(),
                             out.status.data_ptr(),
                             out.iters_run.data_ptr() if out.iters_run is not None else None,
-                            out.sse_trace.data_ptr() if out.sse_trace is not None else None)
+                            out.sse_trace.data_ptr() if out.sse_trace is not None else None,
+                            amax_in.data_ptr() if amax_in is not None else None)
 
 
 def quantize_iter(w: torch.Tensor, params: soar_params, workspace: Optional[torch.Tensor] = None,
@@ -313,6 +315,22 @@ def quantize_batch(descs: Sequence[soar_tensor_desc], params: soar_params, works
     rc = soar_quantize_batch(descs, params, workspace.data_ptr(), workspace.numel(), _stream())
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_quantize_batch")
+
+
+def quantize_rtn_amax(w: torch.Tensor, amax_in: torch.Tensor, workspace: Optional[torch.Tensor] = None,
+                      out: Optional[Quantized] = None) -> Quantized:
+    """Plain NVFP4 (Sec. 3.1) of one tensor with its maximum supplied: a single pass over the data."""
+    rows, cols, _ = _check_matrix(w)
+    if amax_in.dtype != torch.float32 or not amax_in.is_cuda:
+        raise TypeError("amax_in must be a float32 tensor on the GPU")
+    if out is None:
+        out = new_outputs(rows, cols, w.device)
+    p = soar_default_params(SOAR_METHOD_RTN, 0)
+    desc = make_desc(w, out, amax_in)
+    if workspace is None:
+        workspace = new_batch_workspace([desc], p, w.device)
+    quantize_batch([desc], p, workspace)
+    return out
 
 
 def dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:

@@ -92,6 +92,7 @@ struct Task {
     uint32_t *slot_max;      // [kSlots] partial maxima of the absmax kernel, kSlotStride apart
     double   *part;          // [3][kMaxPartials] partial sums N, M, error
     float    *rho;           // [nblk] a / b of the current state, or -Delta^d where b == 0
+    const float *amax_in;    // supplied maximum (plain NVFP4 only), or null: measured by k_absmax
     int32_t  *iters_run;     // iterated path, may be null
     double   *trace;         // iterated path, may be null: iters+1 errors
 };
@@ -666,7 +667,15 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     const uint32_t tid = threadIdx.x;
     const int radius = batch.radius;
     const bool full_search = batch.full_search != 0;
-    const uint32_t amax_bits = t.ctrl->amax_bits;
+    // a supplied maximum that is unusable is read as NaN: the arithmetic below stays defined,
+    // the outputs are unspecified and the status says why
+    bool bad_amax = false;
+    uint32_t amax_bits = t.ctrl->amax_bits;
+    if (METHOD == SOAR_METHOD_RTN && t.amax_in) {
+        const float given = *t.amax_in;
+        bad_amax = !(given > 0.0f) || __float_as_uint(given) >= 0x7F800000u;
+        amax_bits = bad_amax ? 0x7FC00000u : __float_as_uint(given);
+    }
     const bool allzero = amax_bits == 0u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
@@ -736,7 +745,8 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     if (tid == 0) {
         if (t.sse) *t.sse = total;
         if (t.status)
-            *t.status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
+            *t.status = bad_amax ? SOAR_STATUS_BAD_AMAX
+                                 : (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
         if (METHOD == SOAR_METHOD_RTN) *t.gscale = allzero ? 1.0f : alpha0;
     }
     reset_counters(counters, &t.ctrl->top[2]);
@@ -1312,7 +1322,7 @@ hipStream_t aux_stream()
 template <int DT>
 soar_status launch_group(const Batch &b, uint32_t total_wg, int method, hipStream_t st)
 {
-    {
+    if (b.t[0].amax_in == nullptr) {       // all tensors of a batch supply their maximum, or none does
         ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
         hipLaunchKernelGGL(k_absmax<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
@@ -1372,6 +1382,10 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     bool iterated = iterated_params(params);
     for (int32_t k = 0; k < n; ++k) iterated = iterated || descs[k].d_iters_run || descs[k].d_sse_trace;
     if (iterated && params->method != SOAR_METHOD_SOAR) return SOAR_ERR_PARAM;
+    for (int32_t k = 0; k < n; ++k) {
+        if ((descs[k].d_amax_in != nullptr) != (descs[0].d_amax_in != nullptr)) return SOAR_ERR_PARAM;
+        if (descs[k].d_amax_in && params->method != SOAR_METHOD_RTN) return SOAR_ERR_PARAM;
+    }
 
     if (n == 0) return SOAR_OK;
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
@@ -1429,6 +1443,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, tpw);
             t.iters_run = d.d_iters_run;
             t.trace = d.d_sse_trace;
+            t.amax_in = d.d_amax_in;
             t.codes = d.d_codes;
             t.scales = d.d_scales;
             t.gscale = d.d_global_scale;
@@ -1532,6 +1547,7 @@ soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64
     d.d_status = d_status;
     d.d_iters_run = nullptr;
     d.d_sse_trace = nullptr;
+    d.d_amax_in = nullptr;
     return run_batch(1, &d, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 

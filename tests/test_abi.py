@@ -86,6 +86,11 @@ def test_host_side_argument_validation():
         assert _q(q) == 4, field
     d = B.soar_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0x4000, 0, 0, 0x5000, 0)
     assert B.soar_quantize_batch([d], B.soar_default_params(B.SOAR_METHOD_RTN, 0), 0x10000, 1 << 20, 0) == 4
+    # a supplied maximum: plain NVFP4 only, and for every tensor of a batch or for none
+    d = B.soar_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0x4000, 0, 0, 0, 0, 0x5000)
+    e = B.soar_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0x4000, 0, 0, 0, 0, 0)
+    assert B.soar_quantize_batch([d], p, 0x10000, 1 << 20, 0) == 4
+    assert B.soar_quantize_batch([d, e], B.soar_default_params(B.SOAR_METHOD_RTN, 0), 0x10000, 1 << 20, 0) == 4
     d = B.soar_tensor_desc(0x1000, 0, 64, 60, 64, 0x2000, 0x3000, 0x4000, 0, 0)
     assert B.soar_quantize_batch([d], p, 0x10000, 1 << 20, 0) == 2
     assert B.soar_quantize_batch([], p, 0x10000, 1 << 20, 0) == 0
