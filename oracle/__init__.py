@@ -39,7 +39,8 @@ class _Trace(C.Structure):
 
 class _IterParams(C.Structure):
     _fields_ = [("iters", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float), ("beta_hi", C.c_float),
-                ("dd_mode", C.c_int32), ("dss_radius", C.c_int32), ("early_stop_rel", C.c_float)]
+                ("dd_mode", C.c_int32), ("dss_radius", C.c_int32), ("early_stop_rel", C.c_float),
+                ("arm", C.c_int32)]
 
 
 def lib():
@@ -222,21 +223,22 @@ def quantize_rtn_amax(w: np.ndarray, amax: float) -> Quantized:
 
 
 DD_WINDOW, DD_BRACKET = 0, 1
+ARM_SOAR, ARM_CJSO_ONLY, ARM_DSS_ONLY = 0, 1, 2
 
 
 def quantize_iter(w: np.ndarray, iters: int = 15, n_beta: int = 101, beta_lo: float = 0.5,
                   beta_hi: float = 1.5, dd_mode: int = DD_BRACKET, dss_radius: int = 1,
-                  early_stop_rel: float = 1e-3) -> Quantized:
+                  early_stop_rel: float = 1e-3, arm: int = 0) -> Quantized:
     """Algorithm 1 in full (defaults: the paper's settings).  The returned trace holds
     ``sse_trace`` (error of the Eq. 1-2 state, then after every iteration run) and
-    ``iters_run``."""
+    ``iters_run``.  arm: ARM_SOAR, ARM_CJSO_ONLY or ARM_DSS_ONLY (the ablation arms)."""
     rows, cols, ld = _check2d(w)
     dt = _dtype_of(w)
     codes = np.zeros((rows, cols // 2), dtype=np.uint8)
     scales = np.zeros((rows, cols // 16), dtype=np.uint8)
     g, sse, st, it = C.c_float(0.0), C.c_double(0.0), C.c_int32(0), C.c_int32(0)
     tracebuf = np.full(iters + 1, np.nan, dtype=np.float64)
-    p = _IterParams(iters, n_beta, beta_lo, beta_hi, dd_mode, dss_radius, early_stop_rel)
+    p = _IterParams(iters, n_beta, beta_lo, beta_hi, dd_mode, dss_radius, early_stop_rel, arm)
     rc = lib().soar_oracle_quantize_iter(w.ctypes.data, dt, rows, cols, ld, C.byref(p), codes.ctypes.data,
                                          scales.ctypes.data, C.byref(g), C.byref(sse), C.byref(st),
                                          C.byref(it), tracebuf.ctypes.data)

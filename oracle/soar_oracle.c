@@ -477,7 +477,15 @@ typedef struct {
     int32_t dss_radius;      /* K of dd_mode 0                                             */
     float   early_stop_rel;  /* stop when the relative drop of the error is below this
                                 (paper: 1e-3); <= 0 never stops                            */
+    int32_t arm;             /* 0: SOAR (CJSO + DSS);
+                                1: "+CJSO" alone (Sec. 3.2, refinement scheme): Eq. 5, Eq. 6,
+                                   projection onto E4M3, ONE scale for assignment and storage;
+                                   needs n_beta 1, beta 1, dd_mode 0, dss_radius 0;
+                                2: "+DSS" alone (Sec. 3.3 (i)-(ii)): the global scale stays
+                                   at its Eq. 1 value and the search is centred on the block's
+                                   current stored scale instead of Eq. 6                     */
 } soar_oracle_iter_params;
+enum { ORACLE_ARM_SOAR = 0, ORACLE_ARM_CJSO_ONLY = 1, ORACLE_ARM_DSS_ONLY = 2 };
 
 /* largest E4M3 code in [0x01, 0x7E] whose value does not exceed y (0x01 if none) */
 static int e4m3_floor_code(float y)
@@ -513,6 +521,13 @@ static float beta_of(const soar_oracle_iter_params *p, int k)
  * iters = 1, n_beta = 1, beta = 1, dd_mode = 0 the two functions agree bit
  * for bit.
  *
+ * The ablation arms of the paper's component study (p->arm): "+CJSO" alone runs
+ * Eq. 5, Eq. 6 and the E4M3 projection with ONE block scale for assignment and
+ * storage (Sec. 3.2, refinement scheme; alpha and Delta are both updated from
+ * the same assignment, as in the listing's closed-form stage); "+DSS" alone
+ * keeps the Eq. 1 global scale and centres the joint search of Sec. 3.3 (ii)
+ * on the block's current stored scale.
+ *
  * sse_trace (may be NULL): iters+1 doubles; [0] is the error of the Eq. 1-2
  * state, [t+1] the error after iteration t; entries after an early stop are
  * left untouched.  iters_run (may be NULL): iterations carried out.
@@ -529,6 +544,10 @@ int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t co
     if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo)) return -1;
     if (p->dd_mode != 0 && p->dd_mode != 1) return -1;
     if (p->dss_radius < 0 || p->dss_radius > 125) return -1;
+    if (p->arm < ORACLE_ARM_SOAR || p->arm > ORACLE_ARM_DSS_ONLY) return -1;
+    if (p->arm == ORACLE_ARM_CJSO_ONLY &&
+        (p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != 0 || p->dss_radius != 0))
+        return -1;
 
     const int64_t bpr = cols / BLOCK;
     const int64_t nblk = rows * bpr;
@@ -598,7 +617,8 @@ int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t co
         }
         const double N = tree_sum(termN, nblk);
         const double M = tree_sum(termM, nblk);
-        const float alpha_new = (M > 0.0) ? (float)(N / M) : alpha;
+        float alpha_new = (M > 0.0) ? (float)(N / M) : alpha;
+        if (p->arm == ORACLE_ARM_DSS_ONLY) alpha_new = alpha;       /* no closed-form step */
 
         /* ---- Eq. 6 and the joint search of Sec. 3.3 ---- */
 #pragma omp parallel for schedule(static)
@@ -607,8 +627,8 @@ int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t co
             float wv[BLOCK], q[BLOCK], qbest[BLOCK];
             for (int j = 0; j < BLOCK; ++j) wv[j] = load_w(w, dtype, r * ld + cb * BLOCK + j);
             float delta_star;
-            if (b_all[i] == 0.0f)
-                delta_star = soar_oracle_e4m3_value(dd[i]);
+            if (b_all[i] == 0.0f || p->arm == ORACLE_ARM_DSS_ONLY)
+                delta_star = soar_oracle_e4m3_value(dd[i]);         /* centre: the current stored scale */
             else
                 delta_star = (a_all[i] / b_all[i]) / alpha_new;
             /* stored-scale candidates */
@@ -630,6 +650,8 @@ int soar_oracle_quantize_iter(const void *w, int dtype, int64_t rows, int64_t co
             float best_err = 0.0f, best_dq = delta_star;
             for (int k = 0; k < p->n_beta; ++k) {
                 float dq_k = delta_star * beta_of(p, k);
+                if (p->arm == ORACLE_ARM_CJSO_ONLY)                 /* one scale: assign with the projected one */
+                    dq_k = soar_oracle_e4m3_value((uint8_t)cand[0]);
                 assign_codes(wv, alpha_new, dq_k, q);
                 for (int c = 0; c < ncand; ++c) {
                     float err = block_error(wv, q, alpha_new * soar_oracle_e4m3_value((uint8_t)cand[c]));

@@ -63,6 +63,16 @@ MUTANTS += [
     ("iter: trace entry of the wrong iteration", "if (sse_trace) sse_trace[t + 1] = cur;", "if (sse_trace) sse_trace[t + 1] = prev;"),
 ]
 
+# mistakes in the ablation arms (caught by tests/test_oracle_arms.py)
+MUTANTS += [
+    ("arm: +CJSO assigns with the unrounded scale", "if (p->arm == ORACLE_ARM_CJSO_ONLY)                 /* one scale",
+     "if (0)                 /* one scale"),
+    ("arm: +DSS applies the closed-form global scale", "if (p->arm == ORACLE_ARM_DSS_ONLY) alpha_new = alpha;", ";"),
+    ("arm: +DSS centred on Eq. 6", "if (b_all[i] == 0.0f || p->arm == ORACLE_ARM_DSS_ONLY)", "if (b_all[i] == 0.0f)"),
+    ("arm: +CJSO accepts a beta grid", "(p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != 0 || p->dss_radius != 0))",
+     "(p->beta_lo != 1.0f || p->dd_mode != 0 || p->dss_radius != 0))"),
+]
+
 # mistakes in the supplied-maximum form (caught by tests/test_oracle_rtn_amax.py)
 MUTANTS += [
     ("amax: global scale without M_FP4", "const float alpha = amax / (M_FP4 * M_FP8);", "const float alpha = amax / M_FP8;"),
@@ -84,6 +94,8 @@ def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
     env = dict(os.environ, SOAR_ORACLE_LIB=str(so_file))
     if name.startswith("iter:"):
         files = ["test_oracle_iter.py"]
+    elif name.startswith("arm:"):
+        files = ["test_oracle_arms.py"]
     elif name.startswith("amax:"):
         files = ["test_oracle_rtn_amax.py"]
     else:
