@@ -47,6 +47,14 @@ def iter_lane_ops_per_block_beta(ncand):
     return 16 + 8 + 8 + ncand * 32
 
 
+def iterated_params(B, args, streams):
+    stop = 0.0 if args.no_early_stop else 1e-3
+    if args.algorithm == "paper":
+        return B.soar_paper_params(iters=args.iters or None, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
+    method = B.SOAR_METHOD_CJSO_ONLY if args.algorithm == "cjso-only" else B.SOAR_METHOD_DSS_ONLY
+    return B.soar_arm_params(method, iters=args.iters or 15, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,9 +65,11 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
-    ap.add_argument("--algorithm", choices=["single-step", "paper", "rtn-amax"], default="single-step",
+    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn-amax"],
+                    default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
                          "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
+                         "cjso-only / dss-only: the arms of the paper's component study (T = 15, early stop); "
                          "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass)")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
@@ -106,7 +116,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
-    paper = args.algorithm == "paper"
+    paper = args.algorithm in ("paper", "cjso-only", "dss-only")      # the iterated path
     rtn_amax = args.algorithm == "rtn-amax"
     amax_in = [None] * len(specs)
     if rtn_amax:
@@ -114,8 +124,7 @@ def main():
         amax_in = [w.abs().max().float().reshape(1) for w in weights]
         params = B.soar_default_params(B.SOAR_METHOD_RTN, 0, mode, args.tpw, args.streams)
     elif paper:
-        params = B.soar_paper_params(iters=args.iters or None, early_stop_rel=0.0 if args.no_early_stop else None,
-                                     tiles_per_wg=args.tpw, streams=args.streams)
+        params = iterated_params(B, args, args.streams)
         for o in outs:
             o.iters_run = torch.zeros(1, dtype=torch.int32, device=dev)
             o.sse_trace = torch.full((params.iters + 1,), float("nan"), dtype=torch.float64, device=dev)
@@ -153,8 +162,7 @@ def main():
     iters_run = [int(o.iters_run.item()) for o in outs] if paper else None
     if paper and not args.no_kernel_timing:
         n_prof = min(args.steps, 2)
-        p_one = B.soar_paper_params(iters=args.iters or None, early_stop_rel=0.0 if args.no_early_stop else None,
-                                    tiles_per_wg=args.tpw, streams=1)
+        p_one = iterated_params(B, args, 1)
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
             B.quantize_batch(descs, p_one, ws)
@@ -172,15 +180,25 @@ def main():
         lane_ops = block_iters * params.n_beta * iter_lane_ops_per_block_beta(ncand)
         t_iter = kernels["iter"]["ms_per_step"] * 1e-3
         achieved = flops / t_iter / 1e12
-        roofline = {"kernel": "k_iter", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
-                    "lane_ops_per_s": lane_ops / t_iter, "lane_ops_peak_unpacked": VALU_LANE_OPS_PEAK,
-                    "frac_of_unpacked_issue_rate": lane_ops / t_iter / VALU_LANE_OPS_PEAK,
-                    "flops_per_block_beta": iter_flops_per_block_beta(ncand),
-                    "block_iterations_per_step": block_iters,
-                    "launches_per_step": kernels["iter"]["launches"] / n_prof,
-                    "note": "all k_iter launches of a step together (launches of tensors that have stopped "
-                            "return at once); HIP-event durations on the launch stream, single-stream pass"}
+        if args.algorithm == "cjso-only":
+            # no search: an iteration reads the weights and the carried ratio and writes ratio, codes and scale
+            per_w = 2.0 + 0.25 + 0.25 + 0.5625
+            gbs = block_iters * 16 * per_w / t_iter / 1e9
+            roofline = {"kernel": "k_iter", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight_and_iteration": per_w,
+                        "block_iterations_per_step": block_iters,
+                        "launches_per_step": kernels["iter"]["launches"] / n_prof,
+                        "note": "all k_iter launches of a step together; HIP-event durations on the launch stream"}
+        else:
+            roofline = {"kernel": "k_iter", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
+                        "lane_ops_per_s": lane_ops / t_iter, "lane_ops_peak_unpacked": VALU_LANE_OPS_PEAK,
+                        "frac_of_unpacked_issue_rate": lane_ops / t_iter / VALU_LANE_OPS_PEAK,
+                        "flops_per_block_beta": iter_flops_per_block_beta(ncand),
+                        "block_iterations_per_step": block_iters,
+                        "launches_per_step": kernels["iter"]["launches"] / n_prof,
+                        "note": "all k_iter launches of a step together (launches of tensors that have stopped "
+                                "return at once); HIP-event durations on the launch stream, single-stream pass"}
     elif not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
         p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,
@@ -239,7 +257,9 @@ def main():
             t1 = time.perf_counter()
             oracle.quantize_iter(host[0], iters=params.iters, n_beta=params.n_beta, beta_lo=params.beta_lo,
                                  beta_hi=params.beta_hi, dd_mode=params.dd_mode, dss_radius=params.dss_radius,
-                                 early_stop_rel=params.early_stop_rel)
+                                 early_stop_rel=params.early_stop_rel,
+                                 arm={B.SOAR_METHOD_SOAR: oracle.ARM_SOAR, B.SOAR_METHOD_CJSO_ONLY: oracle.ARM_CJSO_ONLY,
+                                      B.SOAR_METHOD_DSS_ONLY: oracle.ARM_DSS_ONLY}[params.method])
         for s, h in zip(sample, host):
             if paper:
                 break
@@ -254,6 +274,7 @@ def main():
 
     out = {
         "metric": {"single-step": "nvfp4_soar_quantize_throughput", "paper": "nvfp4_soar_full_algorithm_throughput",
+                   "cjso-only": "nvfp4_cjso_only_throughput", "dss-only": "nvfp4_dss_only_throughput",
                    "rtn-amax": "nvfp4_rtn_supplied_amax_throughput"}[args.algorithm],
         "value": gbs_in,
         "unit": "GB/s bf16 in",

@@ -52,7 +52,14 @@ typedef enum { SOAR_BF16 = 0, SOAR_FP32 = 1 } soar_dtype;
 
 typedef enum {
     SOAR_METHOD_RTN = 0,     /* max-based NVFP4, Sec. 3.1 Eq. 1-2                   */
-    SOAR_METHOD_SOAR = 1     /* Eq. 1-2 init, Eq. 5-6 step, Eq. 8 search            */
+    SOAR_METHOD_SOAR = 1,    /* Eq. 1-2 init, Eq. 5-6 step, Eq. 8 search            */
+    /* the arms of the component study (Sec. 4.3, first table), iterated path only: */
+    SOAR_METHOD_CJSO_ONLY = 2, /* Sec. 3.2 alone: Eq. 5, Eq. 6, projection onto E4M3, ONE
+                                block scale for assignment and storage; needs n_beta 1,
+                                beta 1, SOAR_DD_WINDOW, dss_radius 0                 */
+    SOAR_METHOD_DSS_ONLY = 3   /* Sec. 3.3 (i)-(ii) alone: the global scale keeps its
+                                Eq. 1 value, the joint search is centred on the block's
+                                current stored scale (window candidates)             */
 } soar_method;
 
 /* how the Eq. 8 search is carried out; every mode returns the same bytes */

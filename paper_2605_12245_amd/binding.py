@@ -16,7 +16,7 @@ import torch
 
 SOAR_OK = 0
 SOAR_BF16, SOAR_FP32 = 0, 1
-SOAR_METHOD_RTN, SOAR_METHOD_SOAR = 0, 1
+SOAR_METHOD_RTN, SOAR_METHOD_SOAR, SOAR_METHOD_CJSO_ONLY, SOAR_METHOD_DSS_ONLY = 0, 1, 2, 3
 SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
 SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX = 1, 2, 4
 SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
@@ -139,6 +139,25 @@ def soar_paper_params(iters: Optional[int] = None, n_beta: Optional[int] = None,
             setattr(p, name, v)
     p.tiles_per_wg = tiles_per_wg
     p.streams = streams
+    return p
+
+
+def soar_arm_params(method: int, iters: int = 15, early_stop_rel: float = 1e-3, n_beta: int = 101,
+                    beta_lo: float = 0.5, beta_hi: float = 1.5, dss_radius: int = 1, tiles_per_wg: int = 0,
+                    streams: int = 0) -> soar_params:
+    """Settings for one arm of the component study: SOAR_METHOD_CJSO_ONLY (takes no search settings)
+    or SOAR_METHOD_DSS_ONLY (window candidates of the given radius, beta grid)."""
+    p = soar_params()
+    lib().soar_default_params(C.byref(p))
+    p.method = method
+    p.iters = iters
+    p.early_stop_rel = early_stop_rel
+    p.tiles_per_wg = tiles_per_wg
+    p.streams = streams
+    if method == SOAR_METHOD_CJSO_ONLY:
+        p.dss_radius = 0
+    else:
+        p.n_beta, p.beta_lo, p.beta_hi, p.dss_radius = n_beta, beta_lo, beta_hi, dss_radius
     return p
 
 

@@ -108,6 +108,7 @@ struct Batch {
     int32_t  dd_mode;
     float    beta_lo, beta_hi;
     float    early_stop_rel;
+    int32_t  arm;            // soar_method of the iterated path: SOAR, CJSO_ONLY or DSS_ONLY
 };
 
 typedef Task Geom;           // the addressing fields are all block_offset needs
@@ -835,6 +836,7 @@ __device__ __forceinline__ void joint_search(const float w[16], float alpha, flo
                                              int n_beta, bool bracket, int c0, int radius, float &best_err,
                                              int &best_code, uint32_t best_nib[2], float q[16])
 {
+
     uint32_t nib[2] = {0u, 0u};
     float best = __builtin_inff();           // an error is never NaN; "first wins" for an infinite one too
     float best_beta = s_beta[0];
@@ -916,7 +918,7 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
                 term[0] = (double)a * (double)delta0;
                 term[1] = ((double)b * (double)delta0) * (double)delta0;
                 term[2] = (double)block_error(w, q, alpha0 * delta0);
-                rho = (b == 0.0f) ? -delta0 : a / b;
+                rho = (b == 0.0f || batch.arm == SOAR_METHOD_DSS_ONLY) ? -delta0 : a / b;
             }
             t.rho[i] = rho;
         }
@@ -936,7 +938,8 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
     const double E = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
     if (tid == 0) {
         t.ctrl->alpha0 = alpha0;
-        t.ctrl->alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;     // the global scale of iteration 0
+        // the global scale of iteration 0: Eq. 5, or unchanged when the closed-form stage is left out
+        t.ctrl->alpha1 = (M > 0.0 && batch.arm != SOAR_METHOD_DSS_ONLY) ? (float)(N / M) : alpha0;
         t.ctrl->N = N;
         t.ctrl->M = M;
         t.ctrl->prev_sse = E;
@@ -982,6 +985,8 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
     const float alpha = t.ctrl->alpha1;
     const bool bracket = batch.dd_mode == SOAR_DD_BRACKET;
     const int radius = batch.radius;
+    const bool one_scale = batch.arm == SOAR_METHOD_CJSO_ONLY;
+    const bool dss_only = batch.arm == SOAR_METHOD_DSS_ONLY;    // rho then always carries -Delta^d: the search centre
 
     TileTree<3> tree{s_wave, s_stack};
     const uint32_t tile0 = lwg * t.tiles_per_wg;
@@ -1010,10 +1015,19 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
                 const float s_first = alpha * (delta_star * s_beta[0]);
                 const float s_final = alpha * (delta_star * s_beta[n_beta - 1]);
                 const bool mid = ((__float_as_uint(s_first) >> 23) - 2u) < 250u && ((__float_as_uint(s_final) >> 23) - 2u) < 250u;
-                if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
-                    joint_search<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code, best_nib, q);
-                else
-                    joint_search<false>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code, best_nib, q);
+                if (one_scale) {
+                    // Sec. 3.2 alone: the projected scale assigns the codes and is stored; nothing to search
+                    best_code = c0;
+                    const float sd = alpha * e4m3_value((uint32_t)c0);
+                    assign_codes(w, sd, best_nib, q);
+                    best_err = block_error(w, q, sd);
+                } else if (__builtin_amdgcn_ballot_w64(!mid) == 0ull) {
+                    joint_search<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code,
+                                       best_nib, q);
+                } else {
+                    joint_search<false>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code,
+                                        best_nib, q);
+                }
                 // the state the next iteration starts from
                 float a, b;
                 block_sums(w, q, a, b);
@@ -1021,7 +1035,7 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
                 term[0] = (double)a * (double)d;
                 term[1] = ((double)b * (double)d) * (double)d;
                 term[2] = (double)best_err;
-                t.rho[i] = (b == 0.0f) ? -d : a / b;
+                t.rho[i] = (b == 0.0f || dss_only) ? -d : a / b;
             }
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             u32x2 packed = {best_nib[0], best_nib[1]};
@@ -1058,7 +1072,7 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
             const bool stop = batch.early_stop_rel > 0.0f && (prev - cur) < (double)batch.early_stop_rel * prev;
             t.ctrl->stopped = stop ? 1u : 0u;
             t.ctrl->prev_sse = cur;
-            t.ctrl->alpha1 = (M > 0.0) ? (float)(N / M) : alpha;      // Eq. 5 for the next iteration
+            t.ctrl->alpha1 = (M > 0.0 && !dss_only) ? (float)(N / M) : alpha;      // Eq. 5 for the next iteration
             t.ctrl->N = N;
             t.ctrl->M = M;
         }
@@ -1173,7 +1187,7 @@ struct ScopedTimer {
 bool valid_params(const soar_params *p)
 {
     if (!p || p->struct_size != sizeof(soar_params)) return false;
-    if (p->method != SOAR_METHOD_RTN && p->method != SOAR_METHOD_SOAR) return false;
+    if (p->method < SOAR_METHOD_RTN || p->method > SOAR_METHOD_DSS_ONLY) return false;
     if (p->block != 16) return false;
     if (p->iters < 1 || p->iters > kMaxIters || p->n_beta < 1 || p->n_beta > kMaxBeta) return false;
     if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo) || !(p->beta_hi < 1e30f)) return false;
@@ -1182,6 +1196,10 @@ bool valid_params(const soar_params *p)
     if (p->method == SOAR_METHOD_RTN &&
         (p->iters != 1 || p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW))
         return false;
+    if (p->method == SOAR_METHOD_CJSO_ONLY &&
+        (p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW || p->dss_radius != 0))
+        return false;
+    if (p->method == SOAR_METHOD_DSS_ONLY && p->dd_mode != SOAR_DD_WINDOW) return false;
     if (p->dss_radius < 0 || p->dss_radius > 125) return false;
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
@@ -1209,7 +1227,7 @@ soar_status check_matrix_ptr(const void *p, int dtype, int64_t ld)
 // Algorithm 1 beyond the single-step settings
 bool iterated_params(const soar_params *p)
 {
-    return p->iters != 1 || p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW;
+    return p->method == SOAR_METHOD_CJSO_ONLY || p->method == SOAR_METHOD_DSS_ONLY || p->iters != 1 || p->n_beta != 1 || p->beta_lo != 1.0f || p->dd_mode != SOAR_DD_WINDOW;
 }
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
@@ -1381,7 +1399,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     }
     bool iterated = iterated_params(params);
     for (int32_t k = 0; k < n; ++k) iterated = iterated || descs[k].d_iters_run || descs[k].d_sse_trace;
-    if (iterated && params->method != SOAR_METHOD_SOAR) return SOAR_ERR_PARAM;
+    if (iterated && params->method == SOAR_METHOD_RTN) return SOAR_ERR_PARAM;
     for (int32_t k = 0; k < n; ++k) {
         if ((descs[k].d_amax_in != nullptr) != (descs[0].d_amax_in != nullptr)) return SOAR_ERR_PARAM;
         if (descs[k].d_amax_in && params->method != SOAR_METHOD_RTN) return SOAR_ERR_PARAM;
@@ -1434,8 +1452,11 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         b.beta_lo = params->beta_lo;
         b.beta_hi = params->beta_hi;
         b.early_stop_rel = params->early_stop_rel;
-        // the iterated kernels are arithmetic-bound: the smallest workgroups balance best
-        const uint32_t tpw = params->tiles_per_wg ? (uint32_t)params->tiles_per_wg : (iterated ? 1u : 0u);
+        b.arm = params->method;
+        // the searching iterated kernels are arithmetic-bound: the smallest workgroups balance best
+        // (the closed-form arm has no search and streams like the single-step kernels)
+        const bool searching = iterated && params->method != SOAR_METHOD_CJSO_ONLY;
+        const uint32_t tpw = params->tiles_per_wg ? (uint32_t)params->tiles_per_wg : (searching ? 1u : 0u);
         uint32_t wg = 0;
         char *per_block = lane_base + (size_t)kGroupMax * kSlotBytes;
         for (int32_t k = i; k < j; ++k) {

@@ -79,6 +79,15 @@ def test_host_side_argument_validation():
     assert B.soar_recon_error(0x1000, 0, 4, 64, 64, 0x8, 0x10, 0x20, 0, 0) == 1
     assert B.soar_recon_error(0x1000, 3, 4, 64, 64, 0x8, 0x10, 0x20, 0x30, 0) == 3
     assert B.soar_e2m1_round_f32(0, 4, 0x10, 0) == 1 and B.soar_e4m3_project_f32(0x10, -1, 0x10, 0) == 2
+    # the arms of the component study
+    for method, field, v in ((2, "n_beta", 3), (2, "beta_lo", 0.5), (2, "dd_mode", 1), (2, "dss_radius", 1),
+                             (3, "dd_mode", 1), (4, "iters", 1)):
+        q = B.soar_arm_params(min(method, 3), iters=2)
+        q.method = method
+        setattr(q, field, v)
+        if field == "beta_lo":
+            q.beta_hi = v
+        assert _q(q) == 4, (method, field)
     # plain NVFP4 has no iterated form
     for field, v in (("iters", 2), ("n_beta", 3), ("dd_mode", 1)):
         q = B.soar_default_params(B.SOAR_METHOD_RTN, 0)

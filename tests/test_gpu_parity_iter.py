@@ -26,7 +26,9 @@ def host_of(w):
 
 
 def oracle_args(p):
-    return dict(iters=p.iters, n_beta=p.n_beta, beta_lo=p.beta_lo, beta_hi=p.beta_hi, dd_mode=p.dd_mode,
+    arm = {B.SOAR_METHOD_SOAR: oracle.ARM_SOAR, B.SOAR_METHOD_CJSO_ONLY: oracle.ARM_CJSO_ONLY,
+           B.SOAR_METHOD_DSS_ONLY: oracle.ARM_DSS_ONLY}[p.method]
+    return dict(arm=arm, iters=p.iters, n_beta=p.n_beta, beta_lo=p.beta_lo, beta_hi=p.beta_hi, dd_mode=p.dd_mode,
                 dss_radius=p.dss_radius, early_stop_rel=p.early_stop_rel)
 
 
@@ -71,8 +73,10 @@ def test_loop_reciprocal_equals_the_division_on_its_whole_range():
         assert B.soar_rcp_midrange_f32(x.data_ptr(), chunk, out.data_ptr(), 0) == 0
         got = out.cpu().numpy().view(np.uint32)
         xh = (np.arange(chunk, dtype=np.uint32) + np.uint32(c)).view(np.float32)
-        want = (one / xh).view(np.uint32)
-        bad = got != want
+        with np.errstate(all="ignore"):
+            want = (one / xh).view(np.uint32)
+        ex = (xh.view(np.uint32) >> np.uint32(23)) & np.uint32(0xFF)
+        bad = (got != want) & (ex >= 1) & (ex <= 252)          # the last chunk reaches past the range
         assert not bad.any(), f"chunk {c:#x}: {np.count_nonzero(bad)} mismatches, first at {xh[bad][:4]}"
 
 
@@ -196,3 +200,42 @@ def test_multi_tensor_workload_scaled_down_two_streams():
     torch.cuda.synchronize()
     for k, (w, o) in enumerate(zip(weights, outs)):
         compare(o, oracle.quantize_iter(host_of(w), **oracle_args(p)), f"tensor {k}")
+
+
+@pytest.mark.parametrize("method", [B.SOAR_METHOD_CJSO_ONLY, B.SOAR_METHOD_DSS_ONLY], ids=["cjso-only", "dss-only"])
+def test_component_study_arms(method):
+    """Sec. 3.2 alone and Sec. 3.3 alone, with and without early stop, on single tensors and in one batch."""
+    for workload, div in ((1, 1), (2, 2), (5, 64)):
+        spec = synth.workload_specs(workload, div)[0]
+        w = synth.make_weight(spec, DEV)
+        for stop in (0.0, 1e-3):
+            p = B.soar_arm_params(method, iters=6, early_stop_rel=stop, n_beta=21, dss_radius=2)
+            out, ref = run_one(w, p, f"arm {method} workload {workload}/{div} stop {stop}")
+            rtn = oracle.quantize(host_of(w), oracle.METHOD_RTN, 0)
+            assert ref.sse < rtn.sse
+            if method == B.SOAR_METHOD_DSS_ONLY:
+                assert ref.global_scale == rtn.global_scale
+    g = torch.Generator(device="cpu").manual_seed(23)
+    ws_list = [synth.make_weight(synth.workload_specs(1, 1)[0], DEV),
+               torch.zeros(16, 64, dtype=torch.bfloat16, device=DEV),
+               (torch.randn(77, 144, generator=g) * 0.1).to(torch.bfloat16).to(DEV),
+               synth.make_weight(synth.workload_specs(5, 64)[0], DEV)]
+    p = B.soar_arm_params(method, iters=5, early_stop_rel=2e-3, n_beta=11, dss_radius=1)
+    outs = [B.new_outputs(w.shape[0], w.shape[1], DEV, p.iters) for w in ws_list]
+    descs = [B.make_desc(w, o) for w, o in zip(ws_list, outs)]
+    ws = B.new_batch_workspace(descs, p, DEV)
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    for k, (w, o) in enumerate(zip(ws_list, outs)):
+        compare(o, oracle.quantize_iter(host_of(w), **oracle_args(p)), f"arm {method} batch tensor {k}")
+
+
+def test_arms_order_as_in_the_convergence_figure():
+    """On the GPU as in the paper's figure: the closed-form steps alone end above the full method."""
+    spec = synth.workload_specs(2, 2)[0]
+    w = synth.make_weight(spec, DEV)
+    full = B.quantize_iter(w, B.soar_paper_params(iters=8, early_stop_rel=0.0))
+    cjso = B.quantize_iter(w, B.soar_arm_params(B.SOAR_METHOD_CJSO_ONLY, iters=8, early_stop_rel=0.0))
+    torch.cuda.synchronize()
+    assert full.sse.item() < cjso.sse.item() < full.sse_trace[0].item()
+    assert cjso.sse_trace[0].item() == full.sse_trace[0].item()
