@@ -65,11 +65,12 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
-    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn-amax"],
+    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax"],
                     default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
                          "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
                          "cjso-only / dss-only: the arms of the paper's component study (T = 15, early stop); "
+                         "rtn: plain NVFP4 (two passes); "
                          "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass)")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
@@ -117,11 +118,12 @@ def main():
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
     paper = args.algorithm in ("paper", "cjso-only", "dss-only")      # the iterated path
-    rtn_amax = args.algorithm == "rtn-amax"
+    rtn_amax = args.algorithm in ("rtn", "rtn-amax")                  # plain NVFP4
     amax_in = [None] * len(specs)
     if rtn_amax:
-        # the supplied maxima: measured here, outside the timed region, as a calibration pass would
-        amax_in = [w.abs().max().float().reshape(1) for w in weights]
+        if args.algorithm == "rtn-amax":
+            # the supplied maxima: measured here, outside the timed region, as a calibration pass would
+            amax_in = [w.abs().max().float().reshape(1) for w in weights]
         params = B.soar_default_params(B.SOAR_METHOD_RTN, 0, mode, args.tpw, args.streams)
     elif paper:
         params = iterated_params(B, args, args.streams)
@@ -223,7 +225,7 @@ def main():
         traffic = None
         if dom == "search" and args.workload == 4 and not args.layers and not rtn_amax:
             traffic = SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
-        if rtn_amax and args.workload == 4 and not args.layers and RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4:
+        if args.algorithm == "rtn-amax" and args.workload == 4 and not args.layers:
             traffic = RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
         roofline = {"kernel": "k_" + dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -263,8 +265,11 @@ def main():
         for s, h in zip(sample, host):
             if paper:
                 break
-            if rtn_amax:
+            if args.algorithm == "rtn-amax":
                 oracle.quantize_rtn_amax(h, float(amax_in[0].item()))
+                continue
+            if args.algorithm == "rtn":
+                oracle.quantize(h, oracle.METHOD_RTN, 0)
                 continue
             oracle.quantize(h, oracle.METHOD_SOAR, s.dss_radius)
         dt = time.perf_counter() - t1
@@ -275,7 +280,7 @@ def main():
     out = {
         "metric": {"single-step": "nvfp4_soar_quantize_throughput", "paper": "nvfp4_soar_full_algorithm_throughput",
                    "cjso-only": "nvfp4_cjso_only_throughput", "dss-only": "nvfp4_dss_only_throughput",
-                   "rtn-amax": "nvfp4_rtn_supplied_amax_throughput"}[args.algorithm],
+                   "rtn": "nvfp4_rtn_throughput", "rtn-amax": "nvfp4_rtn_supplied_amax_throughput"}[args.algorithm],
         "value": gbs_in,
         "unit": "GB/s bf16 in",
         "n_gpus": 1,
