@@ -74,6 +74,10 @@ def parse_args():
                          "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass)")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
+    ap.add_argument("--reps", type=int, default=0,
+                    help="after the timed region: this many separately timed steps, reported as median and min")
+    ap.add_argument("--cold", action="store_true",
+                    help="with --reps: write a 1 GiB scratch buffer before every repetition (caches hold none of the input)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -154,8 +158,31 @@ def main():
     ms_per_step = e0.elapsed_time(e1) / args.steps
     gbs_in = 2.0 * E / (ms_per_step * 1e-3) / 1e9
 
-    sse_soar = sum(float(o.sse.item()) for o in outs)
+    per_tensor_sse = [float(o.sse.item()) for o in outs]
+    sse_soar = sum(per_tensor_sse)
     statuses = [int(o.status.item()) for o in outs]
+
+    # ---- separately timed repetitions (small workloads: median / min, warm or cold)
+    reps = None
+    if args.reps > 0:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
+        times = []
+        for _ in range(args.reps):
+            if scratch is not None:
+                scratch.fill_(1.0)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            step()
+            b.record()
+            torch.cuda.synchronize()
+            times.append(a.elapsed_time(b))
+        times.sort()
+        med = times[len(times) // 2]
+        reps = {"n": args.reps, "cold": bool(args.cold), "median_ms": med, "min_ms": times[0],
+                "median_GBps_bf16_in": 2.0 * E / (med * 1e-3) / 1e9,
+                "median_hbm_frac": (BYTES_SEARCH if args.algorithm == "rtn-amax" else
+                                    4.5625 if args.algorithm == "rtn" else BYTES_3PASS) * E / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
+                if not paper else None}
 
     # ---- per-kernel durations: HIP events around every launch, on the stream it is
     # launched on; same steps again, on one stream so that a kernel's duration is its own
@@ -240,7 +267,9 @@ def main():
         o.iters_run = o.sse_trace = None       # plain descriptors: the single-step entry
     B.quantize_batch([B.make_desc(w, o) for w, o in zip(weights, outs)], p_rtn, ws)
     torch.cuda.synchronize()
-    sse_rtn = sum(float(o.sse.item()) for o in outs)
+    per_tensor_rtn = [float(o.sse.item()) for o in outs]
+    sse_rtn = sum(per_tensor_rtn)
+    ratios = sorted(a / b for a, b in zip(per_tensor_sse, per_tensor_rtn) if b > 0)
 
     # ---- oracle on the host cores, bounded sample of the same workload
     cpu = None
@@ -273,7 +302,26 @@ def main():
                 continue
             oracle.quantize(h, oracle.METHOD_SOAR, s.dss_radius)
         dt = time.perf_counter() - t1
+        # one thread, a slice of the first tensor: nanoseconds per weight of the same function
+        nthreads = oracle.threads()
+        rows1 = max(1, min(host[0].shape[0], (1 << 20) // host[0].shape[1]))
+        piece = np.ascontiguousarray(host[0][:rows1])
+        oracle.set_threads(1)
+        t2 = time.perf_counter()
+        if paper:
+            oracle.quantize_iter(piece, iters=1, n_beta=params.n_beta, beta_lo=params.beta_lo, beta_hi=params.beta_hi,
+                                 dd_mode=params.dd_mode, dss_radius=params.dss_radius, early_stop_rel=0.0,
+                                 arm={B.SOAR_METHOD_SOAR: oracle.ARM_SOAR, B.SOAR_METHOD_CJSO_ONLY: oracle.ARM_CJSO_ONLY,
+                                      B.SOAR_METHOD_DSS_ONLY: oracle.ARM_DSS_ONLY}[params.method])
+        elif rtn_amax:
+            oracle.quantize(piece, oracle.METHOD_RTN, 0)
+        else:
+            oracle.quantize(piece, oracle.METHOD_SOAR, K)
+        ns1 = (time.perf_counter() - t2) * 1e9 / piece.size
+        oracle.set_threads(nthreads)
         cpu = {"value": 2.0 * n_el / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(),
+               "single_thread_ns_per_weight": ns1,
+               "single_thread_note": "one iteration" if paper else "whole path",
                "kind": "oracle", "seconds": dt, "weights_per_s": n_el / dt,
                "sample": f"first {len(sample)} tensor(s) of the workload ({n_el} weights), whole path"}
 
@@ -304,7 +352,9 @@ def main():
         "hbm_frac_3pass": (BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS) if not rtn_amax else None,
         "hbm_frac_single_touch": BYTES_SEARCH * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mse_vs_rtn": sse_soar / sse_rtn if sse_rtn > 0 else None,
+        "mse_vs_rtn_per_tensor_min_median_max": [ratios[0], ratios[len(ratios) // 2], ratios[-1]] if ratios else None,
         "sse_soar": sse_soar, "sse_rtn": sse_rtn,
+        "repetitions": reps,
         "status_bits_or": int(np_or(statuses)),
         "wall_ms_per_step": wall_ms / args.steps,
         "gen_seconds": gen_s,

@@ -392,10 +392,13 @@ __device__ __forceinline__ uint32_t find_task(const Batch &b, uint32_t &lwg)
 
 // ------------------------------------------------------------------ kernels
 // clears the control words, arrival counters and partial maxima of every slot
+constexpr int kInitSplit = 8;             // workgroups per slot
+static_assert(kZeroedBytes % 16 == 0, "control region is cleared with 16-byte stores");
 __global__ __launch_bounds__(kWG) void k_init(char *slots_base)
 {
-    uint32_t *p = reinterpret_cast<uint32_t *>(slots_base + (size_t)blockIdx.x * kSlotBytes);
-    for (uint32_t k = threadIdx.x; k < kZeroedBytes / 4; k += kWG) p[k] = 0u;
+    uint4 *p = reinterpret_cast<uint4 *>(slots_base + (size_t)(blockIdx.x / kInitSplit) * kSlotBytes);
+    for (uint32_t k = (blockIdx.x % kInitSplit) * kWG + threadIdx.x; k < kZeroedBytes / 16; k += kInitSplit * kWG)
+        p[k] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // max |w| over a tensor.  |bits| of finite floats order like the values; NaN
@@ -1429,7 +1432,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     {
         ScopedTimer t(SOAR_KERNEL_INIT, st);
         for (int l = 0; l < lanes && result == SOAR_OK; ++l) {
-            hipLaunchKernelGGL(k_init, dim3(kGroupMax), dim3(kWG), 0, st, base + (size_t)l * lane_bytes);
+            hipLaunchKernelGGL(k_init, dim3(kGroupMax * kInitSplit), dim3(kWG), 0, st, base + (size_t)l * lane_bytes);
             if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
         }
     }
