@@ -78,6 +78,13 @@ def lib():
         L.soar_oracle_quantize_rtn_amax.argtypes = [
             C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_float,
             C.c_void_p, C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.soar_oracle_mxfp4_quantize.restype = C.c_int
+        L.soar_oracle_mxfp4_quantize.argtypes = [
+            C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int32, C.c_float, C.c_float,
+            C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.soar_oracle_mxfp4_dequantize.restype = C.c_int
+        L.soar_oracle_mxfp4_dequantize.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
         L.soar_oracle_dequantize.restype = C.c_int
         L.soar_oracle_dequantize.argtypes = [
             C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
@@ -220,6 +227,34 @@ def quantize_rtn_amax(w: np.ndarray, amax: float) -> Quantized:
     if rc != 0:
         raise ValueError("soar_oracle_quantize_rtn_amax: bad argument")
     return Quantized(codes, scales, np.float32(g.value), float(sse.value), int(st.value), None)
+
+
+def mxfp4_quantize(w: np.ndarray, dss: bool = False, n_beta: int = 101, beta_lo: float = 0.5,
+                   beta_hi: float = 1.5, radius: int = 1) -> Quantized:
+    """MXFP4 (blocks of 32, E8M0 scale bytes), plain or with the decoupled scale search.
+    The returned global_scale is 1 (the format has none)."""
+    rows, cols, ld = _check2d(w)
+    codes = np.zeros((rows, cols // 2), dtype=np.uint8)
+    scales = np.zeros((rows, cols // 32), dtype=np.uint8)
+    sse, st = C.c_double(0.0), C.c_int32(0)
+    rc = lib().soar_oracle_mxfp4_quantize(w.ctypes.data, _dtype_of(w), rows, cols, ld, 1 if dss else 0, n_beta,
+                                          beta_lo, beta_hi, radius, codes.ctypes.data, scales.ctypes.data,
+                                          C.byref(sse), C.byref(st))
+    if rc != 0:
+        raise ValueError("soar_oracle_mxfp4_quantize: bad argument")
+    return Quantized(codes, scales, np.float32(1.0), float(sse.value), int(st.value), None)
+
+
+def mxfp4_dequantize(codes: np.ndarray, scales: np.ndarray, out_dtype: int = FP32) -> np.ndarray:
+    rows, cols = scales.shape[0], scales.shape[1] * 32
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    out = np.zeros((rows, cols), dtype=np.uint16 if out_dtype == BF16 else np.float32)
+    rc = lib().soar_oracle_mxfp4_dequantize(codes.ctypes.data, scales.ctypes.data, rows, cols, out_dtype,
+                                            out.ctypes.data, cols)
+    if rc != 0:
+        raise ValueError("soar_oracle_mxfp4_dequantize: bad argument")
+    return out
 
 
 DD_WINDOW, DD_BRACKET = 0, 1

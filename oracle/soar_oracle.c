@@ -818,3 +818,156 @@ void soar_oracle_set_threads(int n)
     (void)n;
 #endif
 }
+
+/* ------------------------------------------------------------------------- */
+/* Decoupled Scale Search on MXFP4 (Sec. 4.3, "DSS on MXFP4")                  */
+/* ------------------------------------------------------------------------- */
+/*
+ * The paper applies DSS to MXFP4 without restating the format; it is taken
+ * from the public OCP Microscaling Formats specification (v1.0): blocks of 32
+ * E2M1 elements along a row share one E8M0 scale X = 2^(e-127), e in [0, 254]
+ * (255 encodes NaN and is never produced); there is no tensor-wide scale.
+ *
+ * Baseline conversion (that specification, Sec. 6.3):
+ *     shared exponent = floor(log2 max|W_i|) - 2     (2 = exponent of the largest
+ *     E2M1 value 6 = 1.5 * 2^2), clamped to [-127, 127];
+ *     codes = Q_FP4(W_i / X), round to nearest even, saturating at +-6
+ * (a block maximum in (6X, 8X) saturates: that is the format's own behaviour).
+ * A block of zeros takes X = 1 (e = 127).
+ *
+ * DSS (Sec. 3.3 carried over; no closed-form step exists without a global
+ * scale, so this is the "+DSS" arm): the stored scale Delta^d is searched over
+ * the E8M0 codes e0-K .. e0+K around the baseline code e0 (order 0,-1,+1,...,
+ * codes outside [0, 254] skipped), the assignment scale over Delta^q = X0 beta_k,
+ * beta_k as in soar_oracle_quantize_iter, beta ascending (outer loop); a later
+ * pair wins only if strictly better in binary32.  Error of a pair: Eq. 8 with
+ * alpha = 1 over the 32 elements, one ascending chain of fused operations.
+ *
+ * codes: rows*cols/2 bytes (nibble layout as for NVFP4); scales: rows*cols/32
+ * E8M0 bytes.  status: ORACLE_STATUS_NONFINITE if any value is NaN or Inf
+ * (outputs then unspecified).  Returns 0, or -1 on a bad argument.
+ */
+#define MX_BLOCK 32
+#define MX_EMAX_ELEM 2
+
+static float e8m0_value(int e) { return ldexpf(1.0f, e - 127); }
+
+static float mx_block_error(const float *wv, const float *q, float s)
+{
+    float err = 0.0f;
+    for (int j = 0; j < MX_BLOCK; ++j) {
+        float e = fmaf(-q[j], s, wv[j]);
+        err = fmaf(e, e, err);
+    }
+    return err;
+}
+
+static void mx_assign(const float *wv, float scale, float *q)
+{
+    float r = 1.0f / scale;
+    for (int j = 0; j < MX_BLOCK; ++j)
+        q[j] = soar_oracle_e2m1_round(wv[j] * r);
+}
+
+int soar_oracle_mxfp4_quantize(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld,
+                               int dss, int32_t n_beta, float beta_lo, float beta_hi, int32_t radius,
+                               uint8_t *codes, uint8_t *scales, double *sse, int32_t *status)
+{
+    if (!w || !codes || !scales) return -1;
+    if (rows <= 0 || cols <= 0 || cols % MX_BLOCK != 0 || ld < cols) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP32) return -1;
+    if (dss != 0 && dss != 1) return -1;
+    if (dss && (n_beta < 1 || n_beta > 4096 || !(beta_lo > 0.0f) || !(beta_hi >= beta_lo) || radius < 0 || radius > 127))
+        return -1;
+    const int64_t bpr = cols / MX_BLOCK;
+    const int64_t nblk = rows * bpr;
+    double *errs = (double *)malloc(sizeof(double) * (size_t)nblk);
+    if (!errs) return -1;
+    soar_oracle_iter_params grid;
+    memset(&grid, 0, sizeof grid);
+    grid.n_beta = n_beta;
+    grid.beta_lo = beta_lo;
+    grid.beta_hi = beta_hi;
+    int nonfinite = 0;
+#pragma omp parallel for schedule(static) reduction(| : nonfinite)
+    for (int64_t i = 0; i < nblk; ++i) {
+        int64_t r = i / bpr, cb = i % bpr;
+        float wv[MX_BLOCK], q[MX_BLOCK], qbest[MX_BLOCK];
+        float bmax = 0.0f;
+        for (int j = 0; j < MX_BLOCK; ++j) {
+            wv[j] = load_w(w, dtype, r * ld + cb * MX_BLOCK + j);
+            if (!isfinite(wv[j])) nonfinite = 1;
+            else if (fabsf(wv[j]) > bmax) bmax = fabsf(wv[j]);
+        }
+        int e0 = 127;
+        if (bmax > 0.0f) {
+            int ex;
+            (void)frexpf(bmax, &ex);                 /* bmax = m * 2^ex, m in [0.5, 1): floor(log2) = ex - 1 */
+            int shared = (ex - 1) - MX_EMAX_ELEM;
+            if (shared < -127) shared = -127;
+            if (shared > 127) shared = 127;
+            e0 = shared + 127;
+        }
+        const float x0 = e8m0_value(e0);
+        int best_code = e0;
+        float best_err;
+        if (!dss) {
+            mx_assign(wv, x0, qbest);
+            best_err = mx_block_error(wv, qbest, x0);
+        } else {
+            int have = 0;
+            best_err = 0.0f;
+            for (int k = 0; k < n_beta; ++k) {
+                mx_assign(wv, x0 * beta_of(&grid, k), q);
+                for (int c = 0; c <= 2 * radius; ++c) {
+                    int o = (c + 1) / 2;
+                    int code = (c & 1) ? e0 - o : e0 + o;
+                    if (code < 0 || code > 254) continue;
+                    float err = mx_block_error(wv, q, e8m0_value(code));
+                    if (!have || err < best_err) {
+                        have = 1;
+                        best_err = err;
+                        best_code = code;
+                        memcpy(qbest, q, sizeof qbest);
+                    }
+                }
+            }
+        }
+        scales[i] = (uint8_t)best_code;
+        errs[i] = (double)best_err;
+        for (int k = 0; k < MX_BLOCK / 2; ++k) {
+            uint8_t lo = soar_oracle_e2m1_nibble_of_value(copysignf(fabsf(qbest[2 * k]), wv[2 * k]));
+            uint8_t hi = soar_oracle_e2m1_nibble_of_value(copysignf(fabsf(qbest[2 * k + 1]), wv[2 * k + 1]));
+            codes[i * (MX_BLOCK / 2) + k] = (uint8_t)(lo | (hi << 4));
+        }
+    }
+    if (sse) *sse = tree_sum(errs, nblk);
+    if (status) *status = nonfinite ? ORACLE_STATUS_NONFINITE : 0;
+    free(errs);
+    return 0;
+}
+
+/* w^_ij = q_ij * X_i (exact in binary32 unless it underflows); out_dtype BF16 rounds to nearest even. */
+int soar_oracle_mxfp4_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t rows, int64_t cols,
+                                 int out_dtype, void *out, int64_t ld)
+{
+    if (!codes || !scales || !out) return -1;
+    if (rows <= 0 || cols <= 0 || cols % MX_BLOCK != 0 || ld < cols) return -1;
+    if (out_dtype != ORACLE_BF16 && out_dtype != ORACLE_FP32) return -1;
+    const int64_t bpr = cols / MX_BLOCK;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows * bpr; ++i) {
+        int64_t r = i / bpr, cb = i % bpr;
+        if (scales[i] == 255) continue;
+        float s = e8m0_value(scales[i]);
+        for (int j = 0; j < MX_BLOCK; ++j) {
+            uint8_t byte = codes[i * (MX_BLOCK / 2) + j / 2];
+            uint8_t nib = (j & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+            float v = soar_oracle_e2m1_value(nib) * s;
+            int64_t o = r * ld + cb * MX_BLOCK + j;
+            if (out_dtype == ORACLE_BF16) ((uint16_t *)out)[o] = soar_oracle_f32_to_bf16(v);
+            else ((float *)out)[o] = v;
+        }
+    }
+    return 0;
+}

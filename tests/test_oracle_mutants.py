@@ -73,6 +73,20 @@ MUTANTS += [
      "(p->beta_lo != 1.0f || p->dd_mode != 0 || p->dss_radius != 0))"),
 ]
 
+# mistakes in the MXFP4 functions (caught by tests/test_oracle_mxfp4.py)
+MUTANTS += [
+    ("mx: element exponent 3 instead of 2", "#define MX_EMAX_ELEM 2", "#define MX_EMAX_ELEM 3"),
+    ("mx: floor(log2) off by one", "int shared = (ex - 1) - MX_EMAX_ELEM;", "int shared = ex - MX_EMAX_ELEM;"),
+    ("mx: E8M0 bias 128", "static float e8m0_value(int e) { return ldexpf(1.0f, e - 127); }",
+     "static float e8m0_value(int e) { return ldexpf(1.0f, e - 128); }"),
+    ("mx: codes assigned with the stored candidate (not decoupled)", "mx_assign(wv, x0 * beta_of(&grid, k), q);",
+     "mx_assign(wv, e8m0_value(e0) , q);"),
+    ("mx: search only downwards", "int code = (c & 1) ? e0 - o : e0 + o;", "int code = e0 - o;"),
+    ("mx: later pair wins ties", "float err = mx_block_error(wv, q, e8m0_value(code));\n                    if (!have || err < best_err) {",
+     "float err = mx_block_error(wv, q, e8m0_value(code));\n                    if (!have || err <= best_err) {"),
+    ("mx: dequantize without the scale", "        float s = e8m0_value(scales[i]);", "        float s = 1.0f;"),
+]
+
 # mistakes in the supplied-maximum form (caught by tests/test_oracle_rtn_amax.py)
 MUTANTS += [
     ("amax: global scale without M_FP4", "const float alpha = amax / (M_FP4 * M_FP8);", "const float alpha = amax / M_FP8;"),
@@ -94,6 +108,8 @@ def test_every_planted_mistake_is_caught(tmp_path, name, old, new):
     env = dict(os.environ, SOAR_ORACLE_LIB=str(so_file))
     if name.startswith("iter:"):
         files = ["test_oracle_iter.py"]
+    elif name.startswith("mx:"):
+        files = ["test_oracle_mxfp4.py"]
     elif name.startswith("arm:"):
         files = ["test_oracle_arms.py"]
     elif name.startswith("amax:"):
