@@ -18,7 +18,10 @@ MUTANTS = [
     ("e4m3 subnormal spacing", "if (E < -6) E = -6;              /* below", "if (E < -7) E = -7;              /* below"),
     ("alpha0 without M_FP4", "const float alpha0 = amax / (M_FP4 * M_FP8);", "const float alpha0 = amax / M_FP8;"),
     ("block scale without M_FP4", "uint8_t c0 = soar_oracle_e4m3_project(bmax / alpha0_m);", "uint8_t c0 = soar_oracle_e4m3_project(bmax / alpha0);"),
-    ("error with wrong sign", "float e = fmaf(-q[j], s, wv[j]);", "float e = fmaf(q[j], s, wv[j]);"),
+    ("error with wrong sign", "for (int j = 0; j < BLOCK; ++j) {\n        float e = fmaf(-q[j], s, wv[j]);",
+     "for (int j = 0; j < BLOCK; ++j) {\n        float e = fmaf(q[j], s, wv[j]);"),
+    ("mx: error with wrong sign", "for (int j = 0; j < MX_BLOCK; ++j) {\n        float e = fmaf(-q[j], s, wv[j]);",
+     "for (int j = 0; j < MX_BLOCK; ++j) {\n        float e = fmaf(q[j], s, wv[j]);"),
     ("Eq. 5 denominator with Delta instead of Delta^2",
      "termM[i] = ((double)b * (double)delta0) * (double)delta0;", "termM[i] = (double)b * (double)delta0;"),
     ("Eq. 5 numerator without Delta", "termN[i] = (double)a * (double)delta0;", "termN[i] = (double)a;"),
