@@ -238,6 +238,58 @@ soar_status soar_e2m1_round_f32(const float *d_x, int64_t n, uint8_t *d_out, voi
 soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream);
 
 /*
+ * ---- Decoupled Scale Search on MXFP4 (Sec. 4.3 of the paper, "DSS on MXFP4") ----
+ *
+ * The paper names the format without restating it; it is taken from the public OCP
+ * Microscaling Formats specification v1.0: blocks of 32 consecutive elements of a
+ * row (cols % 32 == 0) share one E8M0 scale byte e in [0, 254], X = 2^(e-127); the
+ * elements are E2M1 nibbles packed as for NVFP4; there is no tensor-wide scale.
+ * Plain conversion: e0 = clamp(floor(log2 max|W_i|) - 2, -127, 127) + 127 (127 for a
+ * block of zeros), codes = Q_FP4(W_i / X0), saturating.  With dss = 1 the stored
+ * code is searched over e0-K .. e0+K (order 0,-1,+1,...; codes outside [0, 254]
+ * skipped) jointly with the assignment scale X0 * beta_k (beta grid as in
+ * soar_params, ascending), the error of a pair being Eq. 8 with alpha = 1 over the
+ * 32 elements; a later pair wins only if strictly better in binary32.
+ */
+typedef struct {
+    uint32_t struct_size;    /* sizeof(soar_mx_params)                               */
+    int32_t  dss;            /* 0: plain conversion; 1: decoupled scale search       */
+    int32_t  n_beta;         /* 1 .. 4096                                            */
+    float    beta_lo;        /* 0 < beta_lo <= beta_hi                               */
+    float    beta_hi;
+    int32_t  radius;         /* K, 0 .. 127                                          */
+    int32_t  tiles_per_wg;   /* 0 = chosen by the library; a power of two <= 65536   */
+} soar_mx_params;
+
+/* dss = 1, 101 factors in [0.5, 1.5], K = 1 */
+void soar_mx_default_params(soar_mx_params *p);
+
+/* Bytes of device workspace soar_mxfp4_quantize needs (256-byte aligned, no
+ * initialisation needed); 0 on a bad argument. */
+size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_params *params);
+
+/*
+ * d_w       in   rows x cols, bf16 or fp32, leading dimension ld_elems, 16-byte aligned
+ * d_codes   out  rows*cols/2 bytes, 16-byte aligned
+ * d_scales  out  rows*cols/32 E8M0 bytes
+ * d_sse     out  1 double, may be NULL: sum over blocks of the block errors
+ *                (binary32 per block, binary64 adjacent-pair tree over blocks)
+ * d_status  out  1 int32, may be NULL: SOAR_STATUS_NONFINITE if a value is NaN or
+ *                Inf (outputs then unspecified), else 0
+ * One pass over the data; asynchronous on hip_stream.
+ */
+soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols,
+                                int64_t ld_elems, const soar_mx_params *params,
+                                uint8_t *d_codes, uint8_t *d_scales, double *d_sse, int32_t *d_status,
+                                void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* w^_ij = q_ij * X_i; bf16 output rounds to nearest even.  A scale byte 255 (NaN
+ * in E8M0) leaves its block unwritten. */
+soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, int64_t rows,
+                                  int64_t cols, soar_dtype out_dtype, void *d_out, int64_t ld_elems,
+                                  void *hip_stream);
+
+/*
  * The reciprocal used inside the iterated path's search loop (hardware estimate
  * plus one fused Newton step), exposed so that the claim it rests on can be
  * checked exhaustively: for every positive binary32 x whose biased exponent lies
@@ -256,7 +308,7 @@ soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, voi
 typedef enum {
     SOAR_KERNEL_INIT = 0, SOAR_KERNEL_ABSMAX = 1, SOAR_KERNEL_STATS = 2, SOAR_KERNEL_SEARCH = 3,
     SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_ITER_INIT = 6, SOAR_KERNEL_ITER = 7,
-    SOAR_KERNEL_COUNT = 8
+    SOAR_KERNEL_MX = 8, SOAR_KERNEL_COUNT = 9
 } soar_kernel_id;
 void        soar_kernel_timing_enable(int enable);
 soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches);

@@ -21,14 +21,15 @@ SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
 SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX = 1, 2, 4
 SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 (SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
- SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER,
- SOAR_KERNEL_COUNT) = range(9)
+ SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER, SOAR_KERNEL_MX,
+ SOAR_KERNEL_COUNT) = range(10)
 
 EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
     "soar_quantize_batch",
     "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_rcp_midrange_f32",
+    "soar_mx_default_params", "soar_mxfp4_workspace_bytes", "soar_mxfp4_quantize", "soar_mxfp4_dequantize",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
 )
 
@@ -51,6 +52,13 @@ class soar_params(C.Structure):
         ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
         ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32), ("streams", C.c_int32),
         ("dd_mode", C.c_int32),
+    ]
+
+
+class soar_mx_params(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("dss", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float),
+        ("beta_hi", C.c_float), ("radius", C.c_int32), ("tiles_per_wg", C.c_int32),
     ]
 
 
@@ -97,6 +105,15 @@ def lib():
     L.soar_e2m1_round_f32.restype = i32
     L.soar_e4m3_project_f32.argtypes = [vp, i64, vp, vp]
     L.soar_e4m3_project_f32.restype = i32
+    L.soar_mx_default_params.argtypes = [C.POINTER(soar_mx_params)]
+    L.soar_mx_default_params.restype = None
+    L.soar_mxfp4_workspace_bytes.argtypes = [i64, i64, C.POINTER(soar_mx_params)]
+    L.soar_mxfp4_workspace_bytes.restype = C.c_size_t
+    L.soar_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_mx_params), vp, vp, vp, vp, vp,
+                                      C.c_size_t, vp]
+    L.soar_mxfp4_quantize.restype = i32
+    L.soar_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, i32, vp, i64, vp]
+    L.soar_mxfp4_dequantize.restype = i32
     L.soar_rcp_midrange_f32.argtypes = [vp, i64, vp, vp]
     L.soar_rcp_midrange_f32.restype = i32
     L.soar_kernel_timing_enable.argtypes = [C.c_int]
@@ -205,6 +222,33 @@ def soar_e4m3_project_f32(d_x, n, d_out, hip_stream) -> int:
     return int(lib().soar_e4m3_project_f32(d_x, n, d_out, hip_stream))
 
 
+def soar_mx_default_params(dss: bool = True, n_beta: Optional[int] = None, beta_lo: Optional[float] = None,
+                           beta_hi: Optional[float] = None, radius: Optional[int] = None,
+                           tiles_per_wg: int = 0) -> soar_mx_params:
+    p = soar_mx_params()
+    lib().soar_mx_default_params(C.byref(p))
+    p.dss = 1 if dss else 0
+    for name, v in (("n_beta", n_beta), ("beta_lo", beta_lo), ("beta_hi", beta_hi), ("radius", radius)):
+        if v is not None:
+            setattr(p, name, v)
+    p.tiles_per_wg = tiles_per_wg
+    return p
+
+
+def soar_mxfp4_workspace_bytes(rows: int, cols: int, params: soar_mx_params) -> int:
+    return int(lib().soar_mxfp4_workspace_bytes(rows, cols, C.byref(params)))
+
+
+def soar_mxfp4_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales, d_sse, d_status,
+                        d_workspace, workspace_bytes, hip_stream) -> int:
+    return int(lib().soar_mxfp4_quantize(d_w, dtype, rows, cols, ld_elems, C.byref(params), d_codes, d_scales,
+                                         d_sse, d_status, d_workspace, workspace_bytes, hip_stream))
+
+
+def soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream) -> int:
+    return int(lib().soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream))
+
+
 def soar_rcp_midrange_f32(d_x, n, d_out, hip_stream) -> int:
     return int(lib().soar_rcp_midrange_f32(d_x, n, d_out, hip_stream))
 
@@ -250,7 +294,7 @@ def _check_matrix(w: torch.Tensor):
 class Quantized:
     codes: torch.Tensor          # uint8 [rows, cols/2]
     scales: torch.Tensor         # uint8 [rows, cols/16]
-    global_scale: torch.Tensor   # float32 [1]
+    global_scale: Optional[torch.Tensor]   # float32 [1]; None for MXFP4 (the format has none)
     sse: torch.Tensor            # float64 [1]
     status: torch.Tensor         # int32 [1]
     iters_run: Optional[torch.Tensor] = None   # int32 [1], iterated path
@@ -370,3 +414,41 @@ def recon_error(w: torch.Tensor, q: Quantized) -> torch.Tensor:
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_recon_error")
     return sse
+
+
+# ------------------------------------------------------------------ MXFP4
+def mx_new_outputs(rows: int, cols: int, device) -> Quantized:
+    return Quantized(torch.empty((rows, cols // 2), dtype=torch.uint8, device=device),
+                     torch.empty((rows, cols // 32), dtype=torch.uint8, device=device),
+                     None,
+                     torch.empty(1, dtype=torch.float64, device=device),
+                     torch.empty(1, dtype=torch.int32, device=device))
+
+
+def mx_quantize(w: torch.Tensor, params: soar_mx_params, workspace: Optional[torch.Tensor] = None,
+                out: Optional[Quantized] = None) -> Quantized:
+    """MXFP4 conversion of one tensor (plain or with the decoupled scale search); scales are E8M0 bytes."""
+    rows, cols, ld = _check_matrix(w)
+    if out is None:
+        out = mx_new_outputs(rows, cols, w.device)
+    if workspace is None:
+        n = soar_mxfp4_workspace_bytes(rows, cols, params)
+        if n == 0:
+            raise SoarError(2, "soar_mxfp4_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=w.device)
+    rc = soar_mxfp4_quantize(w.data_ptr(), _dtype_code(w), rows, cols, ld, params, out.codes.data_ptr(),
+                             out.scales.data_ptr(), out.sse.data_ptr(), out.status.data_ptr(),
+                             workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_mxfp4_quantize")
+    return out
+
+
+def mx_dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:
+    rows, cols = q.scales.shape[0], q.scales.shape[1] * 32
+    out = torch.empty((rows, cols), dtype=out_dtype, device=q.codes.device)
+    rc = soar_mxfp4_dequantize(q.codes.data_ptr(), q.scales.data_ptr(), rows, cols, _dtype_code(out),
+                               out.data_ptr(), cols, _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_mxfp4_dequantize")
+    return out

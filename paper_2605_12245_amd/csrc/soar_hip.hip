@@ -1083,6 +1083,233 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
     reset_counters(counters, &t.ctrl->top[2]);
 }
 
+// ------------------------------------------------------------------ MXFP4
+// Blocks of 32 elements with an E8M0 scale byte (OCP Microscaling Formats v1.0), plain
+// conversion or with the decoupled scale search of Sec. 3.3 carried over to it (Sec. 4.3,
+// "DSS on MXFP4").  One lane owns one block: four (bf16) or eight (fp32) 128-bit loads.
+// There is no tensor-wide scale, so this is a single pass; the only tensor-wide result is the
+// error sum (exact adjacent-pair tree, as in the iterated path).
+struct MxTask {
+    const void *w;
+    uint8_t  *codes, *scales;
+    double   *sse;
+    int32_t  *status;
+    int64_t  ld;
+    uint32_t bpr;            // 32-element blocks per row
+    uint32_t nblk;
+    uint32_t tiles_per_wg;
+    uint32_t contiguous;
+    uint32_t n_wg;
+    Ctrl     *ctrl;          // amax_bits is used as the "saw a non-finite value" flag
+    uint32_t *counters;
+    double   *part;
+    int32_t  dss, n_beta, radius;
+    float    beta_lo, beta_hi;
+};
+
+// 2^(e-127) for an E8M0 code e in [0, 254]; e = 0 is the binary32 subnormal 2^-127
+__device__ __forceinline__ float e8m0_value(int e) { return f_of(e > 0 ? (uint32_t)e << 23 : 0x00400000u); }
+
+template <bool FAST>
+__device__ __forceinline__ void mx_assign(const float w[32], float scale, uint32_t nib[4], float q[32])
+{
+    const float r = FAST ? rcp_midrange(scale) : 1.0f / scale;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = w[8 * h + j] * r;
+        uint32_t v = nib[h];
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[0], x[1], 1.0f, 0);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[2], x[3], 1.0f, 1);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[4], x[5], 1.0f, 2);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[6], x[7], 1.0f, 3);
+        nib[h] = v;
+        fp4x8_values(v, q + 8 * h);
+    }
+}
+
+// Eq. 8 with alpha = 1 over the 32 elements: one ascending chain of fused operations
+__device__ __forceinline__ float mx_block_error(const float w[32], const float q[32], float s)
+{
+    const float ns = -s;
+    float err = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        float e = __builtin_fmaf(q[j], ns, w[j]);
+        err = __builtin_fmaf(e, e, err);
+    }
+    return err;
+}
+
+// candidate number c of the search order 0,-1,+1,-2,...; a code outside [0, 254] is clamped onto an
+// already evaluated candidate of the same factor and can then never win
+__device__ __forceinline__ int mx_candidate(int e0, int c)
+{
+    const int o = (c + 1) >> 1;
+    return (c & 1) ? max(e0 - o, 0) : min(e0 + o, 254);
+}
+
+template <bool FAST>
+__device__ __forceinline__ void mx_search(const float w[32], int e0, const float *s_beta, int n_beta, int radius,
+                                          float &best_err, int &best_code, uint32_t best_nib[4], float q[32])
+{
+    const float x0 = e8m0_value(e0);
+    uint32_t nib[4] = {0u, 0u, 0u, 0u};
+    float best = __builtin_inff();
+    float best_beta = s_beta[0];
+    for (int kb = 0; kb < n_beta; ++kb) {
+        const float bk = s_beta[kb];
+        mx_assign<FAST>(w, x0 * bk, nib, q);
+        float m = mx_block_error(w, q, x0);
+        for (int c = 1; c <= 2 * radius; ++c) m = fminf(m, mx_block_error(w, q, e8m0_value(mx_candidate(e0, c))));
+        best_beta = (m < best) ? bk : best_beta;             // strictly better only: the first factor keeps a tie
+        best = fminf(best, m);
+    }
+    // the winning factor once more: its codes, and the first stored code that reaches its least error
+    best_nib[0] = best_nib[1] = best_nib[2] = best_nib[3] = 0u;
+    mx_assign<FAST>(w, x0 * best_beta, best_nib, q);
+    best_code = e0;
+    best_err = mx_block_error(w, q, x0);
+    for (int c = 1; c <= 2 * radius; ++c) {
+        const int code = mx_candidate(e0, c);
+        const float e = mx_block_error(w, q, e8m0_value(code));
+        if (e < best_err) { best_err = e; best_code = code; }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_mx(const MxTask t)
+{
+    __shared__ double s_wave[1][4];
+    __shared__ double s_stack[1][32];
+    __shared__ double s_tree[kWG];
+    __shared__ float s_beta[kMaxBeta];
+    __shared__ uint32_t s_last;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t lwg = blockIdx.x;
+    const int n_beta = t.dss ? t.n_beta : 0;
+    for (int k = (int)tid; k < n_beta; k += kWG)
+        s_beta[k] = n_beta <= 1 ? t.beta_lo
+                                : (t.beta_lo * (float)(n_beta - 1 - k) + t.beta_hi * (float)k) / (float)(n_beta - 1);
+    __syncthreads();
+
+    TileTree<1> tree{s_wave, s_stack};
+    bool nonfinite = false;
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
+        const uint32_t i = (tile0 + k) * kWG + tid;
+        double term[1] = {0.0};
+        if (i < t.nblk) {
+            float w[32], q[32];
+            uint32_t nib[4] = {0u, 0u, 0u, 0u};
+            size_t off;
+            if (t.contiguous) {
+                off = (size_t)i * 32;
+            } else {
+                const uint32_t row = i / t.bpr;
+                off = (size_t)row * (size_t)t.ld + (size_t)(i - row * t.bpr) * 32;
+            }
+            load_block<DT, true>(t.w, off, w);
+            load_block<DT, true>(t.w, off + 16, w + 16);
+            uint32_t mbits = 0u;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) mbits = max(mbits, __float_as_uint(w[j]) & 0x7FFFFFFFu);
+            nonfinite = nonfinite || mbits >= 0x7F800000u;
+            const float bmax = f_of(mbits);
+            // bmax = m 2^ex with m in [0.5, 1): floor(log2 bmax) = ex - 1; the largest E2M1 value is 1.5 * 2^2
+            const int ex = __builtin_amdgcn_frexp_expf(bmax);
+            const int e0 = mbits == 0u ? 127 : min(max(ex - 1 - 2, -127), 127) + 127;
+            int code = e0;
+            float err;
+            if (!t.dss) {
+                const float x0 = e8m0_value(e0);
+                mx_assign<false>(w, x0, nib, q);
+                err = mx_block_error(w, q, x0);
+            } else {
+                // the reciprocal shortcut needs the scales X0 beta_k to stay within biased exponents [1, 252]
+                const float s_first = e8m0_value(e0) * s_beta[0], s_final = e8m0_value(e0) * s_beta[n_beta - 1];
+                const bool mid = ((__float_as_uint(s_first) >> 23) - 2u) < 250u && ((__float_as_uint(s_final) >> 23) - 2u) < 250u;
+                if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
+                    mx_search<true>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
+                else
+                    mx_search<false>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
+            }
+            term[0] = (double)err;
+            u32x4 packed = {nib[0], nib[1], nib[2], nib[3]};
+            __builtin_nontemporal_store(packed, reinterpret_cast<u32x4 *>(t.codes) + i);
+            __builtin_nontemporal_store((uint8_t)code, t.scales + i);
+        }
+        tree.add_tile(k, term);
+    }
+    if (nonfinite) {
+        __hip_atomic_fetch_or(&t.ctrl->amax_bits, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0);        // performed before this wave reaches the barrier below
+    }
+    uint32_t *counters = t.counters;
+    if (tid == 0) {
+        publish(t.part + lwg, tree.wg[0]);
+        s_last = 0u;
+    }
+    __syncthreads();          // every lane's flag update has been issued before lane 0 counts the workgroup in
+    if (tid == 0) s_last = arrive_is_last(counters, &t.ctrl->top[0], t.n_wg, lwg) ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    const double total = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
+    if (tid == 0) {
+        const uint32_t flag = __hip_atomic_load(&t.ctrl->amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t.sse) *t.sse = total;
+        if (t.status) *t.status = flag ? SOAR_STATUS_NONFINITE : 0;
+        t.ctrl->amax_bits = 0u;
+    }
+    reset_counters(counters, &t.ctrl->top[0]);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_mx_dequant(const uint8_t *codes, const uint8_t *scales, uint32_t nblk,
+                                                    uint32_t bpr, int64_t ld, uint32_t contiguous, void *out)
+{
+    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    if (i >= nblk) return;
+    const uint32_t e = scales[i];
+    if (e == 255u) return;
+    const float s = e8m0_value((int)e);
+    const uint4 nb = reinterpret_cast<const uint4 *>(codes)[i];
+    float v[32];
+    fp4x8_values(nb.x, v);
+    fp4x8_values(nb.y, v + 8);
+    fp4x8_values(nb.z, v + 16);
+    fp4x8_values(nb.w, v + 24);
+#pragma unroll
+    for (int j = 0; j < 32; ++j) v[j] = v[j] * s;
+    size_t off;
+    if (contiguous) {
+        off = (size_t)i * 32;
+    } else {
+        const uint32_t row = i / bpr;
+        off = (size_t)row * (size_t)ld + (size_t)(i - row * bpr) * 32;
+    }
+    if constexpr (DT == SOAR_BF16) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        uint32_t u[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            f2 in = {v[2 * k], v[2 * k + 1]};
+            bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
+            __builtin_memcpy(&u[k], &o, 4);
+        }
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = make_uint4(u[4 * k], u[4 * k + 1], u[4 * k + 2], u[4 * k + 3]);
+    } else {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    }
+}
+
 // Eq. 3
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
@@ -1502,6 +1729,25 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     return result;
 }
 
+bool valid_mx_params(const soar_mx_params *p)
+{
+    if (!p || p->struct_size != sizeof(soar_mx_params)) return false;
+    if (p->dss != 0 && p->dss != 1) return false;
+    if (p->n_beta < 1 || p->n_beta > kMaxBeta) return false;
+    if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo) || !(p->beta_hi < 1e30f)) return false;
+    if (p->radius < 0 || p->radius > 127) return false;
+    if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    return true;
+}
+
+soar_status check_mx_shape(int64_t rows, int64_t cols, int64_t ld)
+{
+    if (rows <= 0 || cols <= 0 || cols % 32 != 0 || ld < cols) return SOAR_ERR_SHAPE;
+    if (rows > (int64_t)1 << 31 || cols > (int64_t)1 << 31) return SOAR_ERR_SHAPE;
+    if (rows * (cols / 32) > ((int64_t)1 << 31) - 16 * kWG) return SOAR_ERR_SHAPE;
+    return SOAR_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C-ABI
@@ -1648,6 +1894,105 @@ soar_status soar_e4m3_project_f32(const float *d_x, int64_t n, uint8_t *d_out, v
     if (n == 0) return SOAR_OK;
     hipLaunchKernelGGL(k_e4m3_project, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), d_x, n, d_out);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+void soar_mx_default_params(soar_mx_params *p)
+{
+    if (!p) return;
+    std::memset(p, 0, sizeof(*p));
+    p->struct_size = sizeof(soar_mx_params);
+    p->dss = 1;
+    p->n_beta = 101;
+    p->beta_lo = 0.5f;
+    p->beta_hi = 1.5f;
+    p->radius = 1;
+    p->tiles_per_wg = 0;
+}
+
+size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_params *params)
+{
+    if (!valid_mx_params(params) || check_mx_shape(rows, cols, cols) != SOAR_OK) return 0;
+    return kSlotBytes;
+}
+
+soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
+                                const soar_mx_params *params, uint8_t *d_codes, uint8_t *d_scales, double *d_sse,
+                                int32_t *d_status, void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!d_w || !d_codes || !d_scales || !params) return SOAR_ERR_NULL;
+    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    if (!valid_mx_params(params)) return SOAR_ERR_PARAM;
+    soar_status s = check_mx_shape(rows, cols, ld_elems);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(d_w, dtype, ld_elems);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
+    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
+    if (workspace_bytes < kSlotBytes) return SOAR_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+
+    MxTask t;
+    std::memset(&t, 0, sizeof(t));
+    t.w = d_w;
+    t.codes = d_codes;
+    t.scales = d_scales;
+    t.sse = d_sse;
+    t.status = d_status;
+    t.ld = ld_elems;
+    t.bpr = (uint32_t)(cols / 32);
+    t.nblk = (uint32_t)(rows * (cols / 32));
+    t.contiguous = ld_elems == cols ? 1u : 0u;
+    const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
+    // the search is arithmetic-bound (smallest workgroups balance best); the plain conversion streams
+    uint32_t tpw = params->dss ? 1u : 2u;
+    while (tpw > 1 && tpw > tiles) tpw >>= 1;
+    if (params->tiles_per_wg) tpw = (uint32_t)params->tiles_per_wg;
+    while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
+    t.tiles_per_wg = tpw;
+    t.n_wg = (tiles + tpw - 1) / tpw;
+    char *slot = static_cast<char *>(d_workspace);
+    t.ctrl = reinterpret_cast<Ctrl *>(slot);
+    t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
+    t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
+    t.dss = params->dss;
+    t.n_beta = params->n_beta;
+    t.radius = params->radius;
+    t.beta_lo = params->beta_lo;
+    t.beta_hi = params->beta_hi;
+    {
+        ScopedTimer tm(SOAR_KERNEL_INIT, st);
+        hipLaunchKernelGGL(k_init, dim3(kInitSplit), dim3(kWG), 0, st, slot);
+        SOAR_LAUNCH_CHECK();
+    }
+    ScopedTimer tm(SOAR_KERNEL_MX, st);
+    if (dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(t.n_wg), dim3(kWG), 0, st, t);
+    else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(t.n_wg), dim3(kWG), 0, st, t);
+    SOAR_LAUNCH_CHECK();
+    return SOAR_OK;
+}
+
+soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, int64_t rows, int64_t cols,
+                                  soar_dtype out_dtype, void *d_out, int64_t ld_elems, void *hip_stream)
+{
+    if (!d_codes || !d_scales || !d_out) return SOAR_ERR_NULL;
+    if (out_dtype != SOAR_BF16 && out_dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    soar_status s = check_mx_shape(rows, cols, ld_elems);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(d_out, out_dtype, ld_elems);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint32_t nblk = (uint32_t)(rows * (cols / 32));
+    const uint32_t grid = (nblk + kWG - 1) / kWG;
+    ScopedTimer tm(SOAR_KERNEL_DEQUANT, st);
+    if (out_dtype == SOAR_BF16)
+        hipLaunchKernelGGL(k_mx_dequant<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, nblk,
+                           (uint32_t)(cols / 32), ld_elems, ld_elems == cols ? 1u : 0u, d_out);
+    else
+        hipLaunchKernelGGL(k_mx_dequant<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, nblk,
+                           (uint32_t)(cols / 32), ld_elems, ld_elems == cols ? 1u : 0u, d_out);
     SOAR_LAUNCH_CHECK();
     return SOAR_OK;
 }

@@ -112,3 +112,28 @@ def test_product_path_has_no_cpu_route():
         B.quantize(w)
     src = open(os.path.join(ROOT, "paper_2605_12245_amd", "binding.py")).read()
     assert "import oracle" not in src and "from oracle" not in src
+
+
+def test_mxfp4_host_side_argument_validation():
+    p = B.soar_mx_default_params()
+    assert (p.struct_size, p.dss, p.n_beta, p.radius) == (C.sizeof(B.soar_mx_params), 1, 101, 1)
+    n = B.soar_mxfp4_workspace_bytes(4096, 4096, p)
+    assert n > 0 and n % 256 == 0
+    assert B.soar_mxfp4_workspace_bytes(4096, 4080, p) == 0          # cols % 32
+
+    def q(p, d_w=0x1000, dtype=0, rows=64, cols=64, ld=64, codes=0x2000, scales=0x3000, ws=0x10000, ws_bytes=1 << 20):
+        return B.soar_mxfp4_quantize(d_w, dtype, rows, cols, ld, p, codes, scales, 0, 0, ws, ws_bytes, 0)
+
+    assert q(p, d_w=0) == 1 and q(p, codes=0) == 1 and q(p, scales=0) == 1
+    assert q(p, cols=48, ld=48) == 2 and q(p, rows=0) == 2 and q(p, ld=32) == 2
+    assert q(p, dtype=7) == 3
+    assert q(p, d_w=0x1004) == 7 and q(p, codes=0x2008) == 7 and q(p, ld=68) == 7
+    assert q(p, ws=0) == 5 and q(p, ws=0x10010) == 5 and q(p, ws_bytes=64) == 5
+    for field, bad in (("dss", 2), ("n_beta", 0), ("n_beta", 5000), ("beta_lo", 0.0), ("beta_hi", 0.25),
+                       ("radius", -1), ("radius", 128), ("tiles_per_wg", 3), ("struct_size", 8)):
+        r = B.soar_mx_default_params()
+        setattr(r, field, bad)
+        assert q(r) == 4, field
+    assert B.soar_mxfp4_dequantize(0, 0x10, 4, 64, 0, 0x1000, 64, 0) == 1
+    assert B.soar_mxfp4_dequantize(0x10, 0x10, 4, 48, 0, 0x1000, 48, 0) == 2
+    assert B.soar_mxfp4_dequantize(0x18, 0x10, 4, 64, 0, 0x1000, 64, 0) == 7

@@ -1,0 +1,117 @@
+"""GPU-vs-oracle parity of the MXFP4 conversion and its decoupled scale search, through the C-ABI.
+Bar: codes and E8M0 scale bytes bit-exact, error within 1e-6 relative (expected bit-identical:
+both sides use the same binary64 adjacent-pair tree), dequantization bit-exact."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_12245_amd import binding as B
+from paper_2605_12245_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def host_of(w):
+    w = w.detach().cpu().contiguous()
+    return w.view(torch.int16).numpy().view(np.uint16) if w.dtype == torch.bfloat16 else w.numpy()
+
+
+def check(w, p, what):
+    out = B.mx_quantize(w, p)
+    torch.cuda.synchronize()
+    ref = oracle.mxfp4_quantize(host_of(w), bool(p.dss), p.n_beta, p.beta_lo, p.beta_hi, p.radius)
+    assert int(out.status.item()) == ref.status, what
+    if ref.status:
+        return out, ref
+    assert np.array_equal(out.scales.cpu().numpy(), ref.scales), what
+    assert np.array_equal(out.codes.cpu().numpy(), ref.codes), what
+    assert math.isclose(float(out.sse.item()), ref.sse, rel_tol=1e-6), what
+    assert float(out.sse.item()) == ref.sse, what
+    return out, ref
+
+
+@pytest.mark.parametrize("workload,div", [(1, 1), (2, 1), (3, 4)])
+def test_workloads_plain_and_searched(workload, div):
+    spec = synth.workload_specs(workload, div)[0]
+    w = synth.make_weight(spec, DEV)
+    plain, ref0 = check(w, B.soar_mx_default_params(dss=False), f"plain workload {workload}")
+    dss, ref1 = check(w, B.soar_mx_default_params(), f"search workload {workload}")
+    assert ref1.sse < ref0.sse
+    for q, ref in ((plain, ref0), (dss, ref1)):
+        back = B.mx_dequantize(q, torch.bfloat16).cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(back, oracle.mxfp4_dequantize(ref.codes, ref.scales, oracle.BF16))
+        back32 = B.mx_dequantize(q, torch.float32).cpu().numpy()
+        assert np.array_equal(back32, oracle.mxfp4_dequantize(ref.codes, ref.scales, oracle.FP32))
+
+
+@pytest.mark.parametrize("kw", [dict(n_beta=1, beta_lo=1.0, beta_hi=1.0, radius=0), dict(n_beta=21, radius=0),
+                                dict(n_beta=11, radius=3), dict(n_beta=7, beta_lo=0.8, beta_hi=1.3, radius=2),
+                                dict(n_beta=4096, radius=1)],
+                         ids=["trivial", "K0", "K3", "narrow-K2", "4096-betas"])
+def test_parameter_variants(kw):
+    for workload, div in ((1, 1), (5, 64)):
+        spec = synth.workload_specs(workload, div)[0]
+        w = synth.make_weight(spec, DEV)
+        check(w, B.soar_mx_default_params(**kw), f"{kw} workload {workload}")
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 96), (257, 288), (1000, 1056), (5, 8192 * 4 + 32)])
+def test_ragged_shapes_and_launch_shapes(rows, cols):
+    g = torch.Generator(device="cpu").manual_seed(rows * 31 + cols)
+    w = (torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g) * 2) * 0.02)
+    w = w.to(torch.bfloat16).to(DEV)
+    base, _ = check(w, B.soar_mx_default_params(n_beta=15), f"{rows}x{cols}")
+    for tpw in (2, 8):
+        other = B.mx_quantize(w, B.soar_mx_default_params(n_beta=15, tiles_per_wg=tpw))
+        torch.cuda.synchronize()
+        assert torch.equal(base.codes, other.codes) and torch.equal(base.scales, other.scales)
+        assert base.sse.item() == other.sse.item()
+
+
+def test_fp32_strided_extreme_magnitudes_zero_and_non_finite():
+    g = torch.Generator(device="cpu").manual_seed(9)
+    parent = (torch.randn(200, 448, generator=g)).to(DEV)
+    view = parent[:, 64:64 + 320]
+    for dss in (False, True):
+        p = B.soar_mx_default_params(dss=dss, n_beta=9)
+        out = B.mx_new_outputs(200, 320, DEV)
+        ws = torch.empty(B.soar_mxfp4_workspace_bytes(200, 320, p), dtype=torch.uint8, device=DEV)
+        rc = B.soar_mxfp4_quantize(view.data_ptr(), B.SOAR_FP32, 200, 320, view.stride(0), p, out.codes.data_ptr(),
+                                   out.scales.data_ptr(), out.sse.data_ptr(), out.status.data_ptr(), ws.data_ptr(),
+                                   ws.numel(), 0)
+        assert rc == 0
+        torch.cuda.synchronize()
+        ref = oracle.mxfp4_quantize(view.cpu().contiguous().numpy(), dss, 9, 0.5, 1.5, 1)
+        assert np.array_equal(out.codes.cpu().numpy(), ref.codes) and np.array_equal(out.scales.cpu().numpy(), ref.scales)
+        assert float(out.sse.item()) == ref.sse
+    # magnitudes across the whole E8M0 range, zero blocks, signed zeros
+    rows = []
+    for e in (-149, -140, -127, -126, -100, -20, 0, 20, 100, 124, 127):
+        rows.append(torch.randn(64, generator=g) * (2.0 ** e if -127 < e < 127 else 1.0))
+    f = torch.stack(rows).float()
+    f[10] = (torch.rand(64, generator=g) * 2.0 - 1.0) * 1.9 * 2.0 ** 127          # up to the top of binary32, finite
+    assert torch.isfinite(f).all()
+    f[0] = torch.tensor(2.0 ** -149)
+    f[1] = torch.tensor(2.0 ** -140)
+    f[2] = torch.randn(64, generator=g) * 2.0 ** -127
+    f[3, 32:] = 0.0
+    f[4, 5] = -0.0
+    f = f.to(DEV)
+    for dss in (False, True):
+        _, ref = check(f, B.soar_mx_default_params(dss=dss, n_beta=11, radius=2), f"extremes dss={dss}")
+        assert ref.status == 0 and ref.scales.min() == 0 and ref.scales.max() >= 250
+    bad = f.clone()
+    bad[6, 3] = float("inf")
+    out = B.mx_quantize(bad, B.soar_mx_default_params(dss=False))
+    torch.cuda.synchronize()
+    assert int(out.status.item()) == B.SOAR_STATUS_NONFINITE
+    # the flag does not leak into the next call on the same workspace
+    ws = torch.empty(B.soar_mxfp4_workspace_bytes(11, 64, B.soar_mx_default_params()), dtype=torch.uint8, device=DEV)
+    B.mx_quantize(bad, B.soar_mx_default_params(dss=False), ws)
+    again = B.mx_quantize(f, B.soar_mx_default_params(dss=False), ws)
+    torch.cuda.synchronize()
+    assert int(again.status.item()) == 0
