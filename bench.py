@@ -65,13 +65,14 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
-    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax"],
+    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax", "mxfp4", "mxfp4-dss"],
                     default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
                          "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
                          "cjso-only / dss-only: the arms of the paper's component study (T = 15, early stop); "
                          "rtn: plain NVFP4 (two passes); "
-                         "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass)")
+                         "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass); "
+                         "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--reps", type=int, default=0,
@@ -99,6 +100,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()
+
+    if args.algorithm in ("mxfp4", "mxfp4-dss"):
+        return bench_mxfp4(args, torch, B, synth, dev)
 
     specs = synth.workload_specs(args.workload)
     per_layer = {4: 7, 5: 3}.get(args.workload, 1)
@@ -363,6 +367,98 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def bench_mxfp4(args, torch, B, synth, dev):
+    """MXFP4 conversion of every tensor of the workload, one soar_mxfp4_quantize call per tensor."""
+    specs = synth.workload_specs(args.workload)
+    per_layer = {4: 7, 5: 3}.get(args.workload, 1)
+    if args.layers and args.workload in (4, 5):
+        specs = specs[: args.layers * per_layer]
+    dss = args.algorithm == "mxfp4-dss"
+    p = B.soar_mx_default_params(dss=dss, tiles_per_wg=args.tpw)
+    weights = [synth.make_weight(s, dev) for s in specs]
+    outs = [B.mx_new_outputs(s.rows, s.cols, dev) for s in specs]
+    ws = torch.empty(max(B.soar_mxfp4_workspace_bytes(s.rows, s.cols, p) for s in specs), dtype=torch.uint8, device=dev)
+    E = sum(s.numel for s in specs)
+    torch.cuda.synchronize()
+
+    def step(params=p):
+        for w, o in zip(weights, outs):
+            B.mx_quantize(w, params, ws, o)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    sse = sum(float(o.sse.item()) for o in outs)
+    status = np_or(int(o.status.item()) for o in outs)
+
+    kernels, roofline = {}, None
+    if not args.no_kernel_timing:
+        n_prof = min(args.steps, 2 if dss else 5)
+        B.soar_kernel_timing_enable(True)
+        for _ in range(n_prof):
+            step()
+        torch.cuda.synchronize()
+        for kid, nm in ((B.SOAR_KERNEL_INIT, "init"), (B.SOAR_KERNEL_MX, "mx")):
+            ms, n = B.soar_kernel_timing_read(kid)
+            kernels[nm] = {"launches": n, "total_ms": ms, "avg_us": (ms / n * 1e3) if n else None, "ms_per_step": ms / n_prof}
+        B.soar_kernel_timing_enable(False)
+        t_mx = kernels["mx"]["ms_per_step"] * 1e-3
+        if dss:
+            ncand = 2 * p.radius + 1
+            flops = (E // 32) * p.n_beta * (32 + 32 + 32 + ncand * 128)      # products, roundings, decoded values, error pairs
+            achieved = flops / t_mx / 1e12
+            roofline = {"kernel": "k_mx", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
+                        "flops_per_block_and_factor": 32 + 32 + 32 + ncand * 128,
+                        "note": "all k_mx launches of a step together; HIP-event durations on the launch stream"}
+        else:
+            per_w = 2.0 + 0.5 + 1.0 / 32.0
+            gbs = per_w * E / t_mx / 1e9
+            roofline = {"kernel": "k_mx", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
+                        "weights_per_launch": E / len(specs), "avg_launch_us": kernels["mx"]["avg_us"],
+                        "note": "per-launch HIP-event durations on the launch stream, one launch per tensor"}
+
+    # error of the plain conversion, for the ratio the paper's table is about
+    p_plain = B.soar_mx_default_params(dss=False)
+    step(p_plain)
+    torch.cuda.synchronize()
+    sse_plain = sum(float(o.sse.item()) for o in outs)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        h = weights[0].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        if dss:
+            h = np.ascontiguousarray(h[: max(1, h.shape[0] // 4)])
+        t1 = time.perf_counter()
+        oracle.mxfp4_quantize(h, dss, p.n_beta, p.beta_lo, p.beta_hi, p.radius)
+        dt = time.perf_counter() - t1
+        cpu = {"value": 2.0 * h.size / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(), "kind": "oracle",
+               "seconds": dt, "weights_per_s": h.size / dt,
+               "sample": f"first {h.shape[0]} rows of the first tensor ({h.size} weights), whole path"}
+    print(json.dumps({
+        "metric": "mxfp4_dss_quantize_throughput" if dss else "mxfp4_quantize_throughput",
+        "value": 2.0 * E / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s bf16 in", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
+                   "entry_point": "soar_mxfp4_quantize", "input": "bf16, resident in HBM", "algorithm": args.algorithm,
+                   "n_beta": p.n_beta if dss else None, "beta": [p.beta_lo, p.beta_hi] if dss else None,
+                   "radius": p.radius if dss else None},
+        "weights_per_s": E / (ms_per_step * 1e-3), "mse_vs_plain_mxfp4": sse / sse_plain if sse_plain > 0 else None,
+        "sse": sse, "sse_plain": sse_plain, "status_bits_or": status, "kernels": kernels, "roofline": roofline,
+        "cpu_baseline": cpu}))
 
 
 def np_or(xs):
