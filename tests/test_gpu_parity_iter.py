@@ -239,3 +239,27 @@ def test_arms_order_as_in_the_convergence_figure():
     torch.cuda.synchronize()
     assert full.sse.item() < cjso.sse.item() < full.sse_trace[0].item()
     assert cjso.sse_trace[0].item() == full.sse_trace[0].item()
+
+
+def test_full_model_workload_in_the_bench_configuration_sampled_tensors():
+    """Config 4 at full size, enqueued exactly as bench.py --algorithm paper does (one batch, default
+    streams); the oracle checks tensors it can compute one by one: the first, one wide MLP tensor
+    and the last (each tensor's result depends on that tensor alone)."""
+    specs = synth.workload_specs(4)
+    weights = [synth.make_weight(s, DEV) for s in specs]
+    p = B.soar_paper_params()
+    outs = [B.new_outputs(s.rows, s.cols, DEV, p.iters) for s in specs]
+    descs = [B.make_desc(w, o) for w, o in zip(weights, outs)]
+    ws = B.new_batch_workspace(descs, p, DEV)
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    assert all(int(o.status.item()) == 0 for o in outs)
+    assert all(1 <= int(o.iters_run.item()) <= p.iters for o in outs)
+    for k in (0, 130, len(specs) - 1):
+        compare(outs[k], oracle.quantize_iter(host_of(weights[k]), **oracle_args(p)), f"tensor {k} ({specs[k].name})")
+    # properties that hold for every tensor: trace falls from the plain-NVFP4 error, reported error = last entry
+    for k, o in enumerate(outs):
+        tr = o.sse_trace.cpu().numpy()
+        n = int(o.iters_run.item())
+        assert not np.isnan(tr[: n + 1]).any() and np.isnan(tr[n + 1:]).all(), k
+        assert tr[n] < tr[0] and float(o.sse.item()) == tr[n], k

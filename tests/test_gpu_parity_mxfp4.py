@@ -115,3 +115,13 @@ def test_fp32_strided_extreme_magnitudes_zero_and_non_finite():
     again = B.mx_quantize(f, B.soar_mx_default_params(dss=False), ws)
     torch.cuda.synchronize()
     assert int(again.status.item()) == 0
+
+
+def test_full_size_tensors_of_the_model_workload_sampled():
+    """bench.py --algorithm mxfp4-dss calls the entry point once per tensor of config 4; here: the first
+    tensor and one wide MLP tensor at full size, with the default search settings."""
+    specs = synth.workload_specs(4)
+    for k in (0, 4):
+        w = synth.make_weight(specs[k], DEV)
+        check(w, B.soar_mx_default_params(), f"config 4 tensor {k} ({specs[k].name})")
+        check(w, B.soar_mx_default_params(dss=False), f"config 4 tensor {k} plain")

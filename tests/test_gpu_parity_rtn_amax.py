@@ -82,3 +82,23 @@ def test_unusable_maximum_sets_the_status_bit():
         out = B.quantize_rtn_amax(w, torch.tensor([bad], dtype=torch.float32, device=DEV))
         torch.cuda.synchronize()
         assert int(out.status.item()) == B.SOAR_STATUS_BAD_AMAX
+
+
+def test_full_model_workload_in_the_bench_configuration_sampled_tensors():
+    """Config 4 at full size as bench.py --algorithm rtn-amax enqueues it; every 21st tensor against the oracle."""
+    specs = synth.workload_specs(4)
+    weights = [synth.make_weight(s, DEV) for s in specs]
+    am = [w.abs().max().float().reshape(1) for w in weights]
+    p = B.soar_default_params(B.SOAR_METHOD_RTN, 0)
+    outs = [B.new_outputs(s.rows, s.cols, DEV) for s in specs]
+    descs = [B.make_desc(w, o, a) for w, o, a in zip(weights, outs, am)]
+    ws = B.new_batch_workspace(descs, p, DEV)
+    B.quantize_batch(descs, p, ws)
+    torch.cuda.synchronize()
+    assert all(int(o.status.item()) == 0 for o in outs)
+    for k in range(0, len(specs), 21):
+        ref = oracle.quantize_rtn_amax(host_of(weights[k]), float(am[k].item()))
+        assert np.array_equal(outs[k].codes.cpu().numpy(), ref.codes), k
+        assert np.array_equal(outs[k].scales.cpu().numpy(), ref.scales), k
+        assert np.float32(outs[k].global_scale.item()) == ref.global_scale, k
+        assert math.isclose(float(outs[k].sse.item()), ref.sse, rel_tol=1e-6), k
