@@ -283,6 +283,30 @@ soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows,
                                 uint8_t *d_codes, uint8_t *d_scales, double *d_sse, int32_t *d_status,
                                 void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
+/* One tensor of an MXFP4 batch: the arguments of soar_mxfp4_quantize that differ per tensor. */
+typedef struct {
+    const void *d_w;
+    int32_t     dtype;           /* soar_dtype */
+    int64_t     rows, cols, ld_elems;
+    uint8_t    *d_codes;
+    uint8_t    *d_scales;
+    double     *d_sse;           /* may be NULL */
+    int32_t    *d_status;        /* may be NULL */
+} soar_mx_tensor_desc;
+
+/*
+ * soar_mxfp4_quantize for n tensors on one stream with one workspace of at least
+ * soar_mxfp4_batch_workspace_bytes(): up to 8 consecutive tensors of one element
+ * type share a kernel launch; results are those of n separate calls.  `descs` is
+ * HOST memory, not referenced after the call returns; all descriptors are
+ * validated before anything is enqueued.
+ */
+soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *descs,
+                                      const soar_mx_params *params, void *d_workspace,
+                                      size_t workspace_bytes, void *hip_stream);
+size_t soar_mxfp4_batch_workspace_bytes(int32_t n, const soar_mx_tensor_desc *descs,
+                                        const soar_mx_params *params);
+
 /* w^_ij = q_ij * X_i; bf16 output rounds to nearest even.  A scale byte 255 (NaN
  * in E8M0) leaves its block unwritten. */
 soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, int64_t rows,

@@ -30,6 +30,7 @@ EXPORTS = (
     "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_rcp_midrange_f32",
     "soar_mx_default_params", "soar_mxfp4_workspace_bytes", "soar_mxfp4_quantize", "soar_mxfp4_dequantize",
+    "soar_mxfp4_quantize_batch", "soar_mxfp4_batch_workspace_bytes",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
 )
 
@@ -59,6 +60,14 @@ class soar_mx_params(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dss", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float),
         ("beta_hi", C.c_float), ("radius", C.c_int32), ("tiles_per_wg", C.c_int32),
+    ]
+
+
+class soar_mx_tensor_desc(C.Structure):
+    _fields_ = [
+        ("d_w", C.c_void_p), ("dtype", C.c_int32),
+        ("rows", C.c_int64), ("cols", C.c_int64), ("ld_elems", C.c_int64),
+        ("d_codes", C.c_void_p), ("d_scales", C.c_void_p), ("d_sse", C.c_void_p), ("d_status", C.c_void_p),
     ]
 
 
@@ -112,6 +121,11 @@ def lib():
     L.soar_mxfp4_quantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_mx_params), vp, vp, vp, vp, vp,
                                       C.c_size_t, vp]
     L.soar_mxfp4_quantize.restype = i32
+    L.soar_mxfp4_quantize_batch.argtypes = [i32, C.POINTER(soar_mx_tensor_desc), C.POINTER(soar_mx_params), vp,
+                                            C.c_size_t, vp]
+    L.soar_mxfp4_quantize_batch.restype = i32
+    L.soar_mxfp4_batch_workspace_bytes.argtypes = [i32, C.POINTER(soar_mx_tensor_desc), C.POINTER(soar_mx_params)]
+    L.soar_mxfp4_batch_workspace_bytes.restype = C.c_size_t
     L.soar_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, i32, vp, i64, vp]
     L.soar_mxfp4_dequantize.restype = i32
     L.soar_rcp_midrange_f32.argtypes = [vp, i64, vp, vp]
@@ -243,6 +257,18 @@ def soar_mxfp4_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_sca
                         d_workspace, workspace_bytes, hip_stream) -> int:
     return int(lib().soar_mxfp4_quantize(d_w, dtype, rows, cols, ld_elems, C.byref(params), d_codes, d_scales,
                                          d_sse, d_status, d_workspace, workspace_bytes, hip_stream))
+
+
+def soar_mxfp4_quantize_batch(descs: Sequence[soar_mx_tensor_desc], params, d_workspace, workspace_bytes,
+                              hip_stream) -> int:
+    arr = (soar_mx_tensor_desc * len(descs))(*descs)
+    return int(lib().soar_mxfp4_quantize_batch(len(descs), arr, C.byref(params), d_workspace, workspace_bytes,
+                                               hip_stream))
+
+
+def soar_mxfp4_batch_workspace_bytes(descs: Sequence[soar_mx_tensor_desc], params) -> int:
+    arr = (soar_mx_tensor_desc * len(descs))(*descs)
+    return int(lib().soar_mxfp4_batch_workspace_bytes(len(descs), arr, C.byref(params)))
 
 
 def soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream) -> int:
@@ -442,6 +468,24 @@ def mx_quantize(w: torch.Tensor, params: soar_mx_params, workspace: Optional[tor
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_mxfp4_quantize")
     return out
+
+
+def mx_make_desc(w: torch.Tensor, out: Quantized) -> soar_mx_tensor_desc:
+    rows, cols, ld = _check_matrix(w)
+    return soar_mx_tensor_desc(w.data_ptr(), _dtype_code(w), rows, cols, ld, out.codes.data_ptr(),
+                               out.scales.data_ptr(), out.sse.data_ptr(), out.status.data_ptr())
+
+
+def mx_quantize_batch(descs: Sequence[soar_mx_tensor_desc], params: soar_mx_params,
+                      workspace: Optional[torch.Tensor] = None, device=None) -> None:
+    if workspace is None:
+        n = soar_mxfp4_batch_workspace_bytes(descs, params)
+        if n == 0:
+            raise SoarError(2, "soar_mxfp4_batch_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=device or "cuda")
+    rc = soar_mxfp4_quantize_batch(descs, params, workspace.data_ptr(), workspace.numel(), _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_mxfp4_quantize_batch")
 
 
 def mx_dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:

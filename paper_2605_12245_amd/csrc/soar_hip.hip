@@ -1099,12 +1099,18 @@ struct MxTask {
     uint32_t nblk;
     uint32_t tiles_per_wg;
     uint32_t contiguous;
+    uint32_t wg_begin;       // first workgroup of the grid that works on this tensor
     uint32_t n_wg;
     Ctrl     *ctrl;          // amax_bits is used as the "saw a non-finite value" flag
     uint32_t *counters;
     double   *part;
     int32_t  dss, n_beta, radius;
     float    beta_lo, beta_hi;
+};
+
+struct MxBatch {
+    MxTask   t[kGroupMax];
+    uint32_t n;
 };
 
 // 2^(e-127) for an E8M0 code e in [0, 254]; e = 0 is the binary32 subnormal 2^-127
@@ -1179,7 +1185,7 @@ __device__ __forceinline__ void mx_search(const float w[32], int e0, const float
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_mx(const MxTask t)
+__global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
 {
     __shared__ double s_wave[1][4];
     __shared__ double s_stack[1][32];
@@ -1188,7 +1194,11 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxTask t)
     __shared__ uint32_t s_last;
 
     const uint32_t tid = threadIdx.x;
-    const uint32_t lwg = blockIdx.x;
+    uint32_t which = 0;
+    for (uint32_t j = 1; j < batch.n; ++j)
+        if (blockIdx.x >= batch.t[j].wg_begin) which = j;
+    const MxTask t = batch.t[which];
+    const uint32_t lwg = blockIdx.x - t.wg_begin;
     const int n_beta = t.dss ? t.n_beta : 0;
     for (int k = (int)tid; k < n_beta; k += kWG)
         s_beta[k] = n_beta <= 1 ? t.beta_lo
@@ -1917,60 +1927,106 @@ size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_para
     return kSlotBytes;
 }
 
+soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *descs, const soar_mx_params *params,
+                                      void *d_workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (n < 0) return SOAR_ERR_SHAPE;
+    if ((n > 0 && !descs) || !params) return SOAR_ERR_NULL;
+    if (!valid_mx_params(params)) return SOAR_ERR_PARAM;
+    for (int32_t k = 0; k < n; ++k) {
+        const soar_mx_tensor_desc &d = descs[k];
+        if (!d.d_w || !d.d_codes || !d.d_scales) return SOAR_ERR_NULL;
+        if (d.dtype != SOAR_BF16 && d.dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+        soar_status s = check_mx_shape(d.rows, d.cols, d.ld_elems);
+        if (s != SOAR_OK) return s;
+        s = check_matrix_ptr(d.d_w, d.dtype, d.ld_elems);
+        if (s != SOAR_OK) return s;
+        if (reinterpret_cast<uintptr_t>(d.d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
+    }
+    if (n == 0) return SOAR_OK;
+    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
+    const int32_t slots = n < kGroupMax ? n : kGroupMax;
+    if (workspace_bytes < (size_t)slots * kSlotBytes) return SOAR_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *base = static_cast<char *>(d_workspace);
+    {
+        ScopedTimer tm(SOAR_KERNEL_INIT, st);
+        hipLaunchKernelGGL(k_init, dim3(slots * kInitSplit), dim3(kWG), 0, st, base);
+        SOAR_LAUNCH_CHECK();
+    }
+    // consecutive tensors of one element type share a launch (up to kGroupMax); every kernel leaves the
+    // control words of its slots as it found them, so the next group reuses them
+    for (int32_t i = 0; i < n;) {
+        int32_t j = i + 1;
+        while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype) ++j;
+        MxBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.n = (uint32_t)(j - i);
+        uint32_t wg = 0;
+        for (int32_t k = i; k < j; ++k) {
+            const soar_mx_tensor_desc &d = descs[k];
+            MxTask &t = b.t[k - i];
+            t.w = d.d_w;
+            t.codes = d.d_codes;
+            t.scales = d.d_scales;
+            t.sse = d.d_sse;
+            t.status = d.d_status;
+            t.ld = d.ld_elems;
+            t.bpr = (uint32_t)(d.cols / 32);
+            t.nblk = (uint32_t)(d.rows * (d.cols / 32));
+            t.contiguous = d.ld_elems == d.cols ? 1u : 0u;
+            const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
+            // the search is arithmetic-bound (smallest workgroups balance best); the plain conversion streams
+            uint32_t tpw = params->dss ? 1u : 2u;
+            while (tpw > 1 && tpw > tiles) tpw >>= 1;
+            if (params->tiles_per_wg) tpw = (uint32_t)params->tiles_per_wg;
+            while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
+            t.tiles_per_wg = tpw;
+            t.n_wg = (tiles + tpw - 1) / tpw;
+            t.wg_begin = wg;
+            wg += t.n_wg;
+            char *slot = base + (size_t)(k - i) * kSlotBytes;
+            t.ctrl = reinterpret_cast<Ctrl *>(slot);
+            t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
+            t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
+            t.dss = params->dss;
+            t.n_beta = params->n_beta;
+            t.radius = params->radius;
+            t.beta_lo = params->beta_lo;
+            t.beta_hi = params->beta_hi;
+        }
+        ScopedTimer tm(SOAR_KERNEL_MX, st);
+        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), 0, st, b);
+        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), 0, st, b);
+        SOAR_LAUNCH_CHECK();
+        i = j;
+    }
+    return SOAR_OK;
+}
+
+size_t soar_mxfp4_batch_workspace_bytes(int32_t n, const soar_mx_tensor_desc *descs, const soar_mx_params *params)
+{
+    if (n <= 0 || !descs || !valid_mx_params(params)) return 0;
+    for (int32_t k = 0; k < n; ++k)
+        if (check_mx_shape(descs[k].rows, descs[k].cols, descs[k].ld_elems) != SOAR_OK) return 0;
+    return (size_t)(n < kGroupMax ? n : kGroupMax) * kSlotBytes;
+}
+
 soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
                                 const soar_mx_params *params, uint8_t *d_codes, uint8_t *d_scales, double *d_sse,
                                 int32_t *d_status, void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
-    if (!d_w || !d_codes || !d_scales || !params) return SOAR_ERR_NULL;
-    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
-    if (!valid_mx_params(params)) return SOAR_ERR_PARAM;
-    soar_status s = check_mx_shape(rows, cols, ld_elems);
-    if (s != SOAR_OK) return s;
-    s = check_matrix_ptr(d_w, dtype, ld_elems);
-    if (s != SOAR_OK) return s;
-    if (reinterpret_cast<uintptr_t>(d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
-    if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
-    if (workspace_bytes < kSlotBytes) return SOAR_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-
-    MxTask t;
-    std::memset(&t, 0, sizeof(t));
-    t.w = d_w;
-    t.codes = d_codes;
-    t.scales = d_scales;
-    t.sse = d_sse;
-    t.status = d_status;
-    t.ld = ld_elems;
-    t.bpr = (uint32_t)(cols / 32);
-    t.nblk = (uint32_t)(rows * (cols / 32));
-    t.contiguous = ld_elems == cols ? 1u : 0u;
-    const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
-    // the search is arithmetic-bound (smallest workgroups balance best); the plain conversion streams
-    uint32_t tpw = params->dss ? 1u : 2u;
-    while (tpw > 1 && tpw > tiles) tpw >>= 1;
-    if (params->tiles_per_wg) tpw = (uint32_t)params->tiles_per_wg;
-    while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
-    t.tiles_per_wg = tpw;
-    t.n_wg = (tiles + tpw - 1) / tpw;
-    char *slot = static_cast<char *>(d_workspace);
-    t.ctrl = reinterpret_cast<Ctrl *>(slot);
-    t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
-    t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
-    t.dss = params->dss;
-    t.n_beta = params->n_beta;
-    t.radius = params->radius;
-    t.beta_lo = params->beta_lo;
-    t.beta_hi = params->beta_hi;
-    {
-        ScopedTimer tm(SOAR_KERNEL_INIT, st);
-        hipLaunchKernelGGL(k_init, dim3(kInitSplit), dim3(kWG), 0, st, slot);
-        SOAR_LAUNCH_CHECK();
-    }
-    ScopedTimer tm(SOAR_KERNEL_MX, st);
-    if (dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(t.n_wg), dim3(kWG), 0, st, t);
-    else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(t.n_wg), dim3(kWG), 0, st, t);
-    SOAR_LAUNCH_CHECK();
-    return SOAR_OK;
+    soar_mx_tensor_desc d;
+    d.d_w = d_w;
+    d.dtype = dtype;
+    d.rows = rows;
+    d.cols = cols;
+    d.ld_elems = ld_elems;
+    d.d_codes = d_codes;
+    d.d_scales = d_scales;
+    d.d_sse = d_sse;
+    d.d_status = d_status;
+    return soar_mxfp4_quantize_batch(1, &d, params, d_workspace, workspace_bytes, hip_stream);
 }
 
 soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, int64_t rows, int64_t cols,

@@ -134,6 +134,13 @@ def test_mxfp4_host_side_argument_validation():
         r = B.soar_mx_default_params()
         setattr(r, field, bad)
         assert q(r) == 4, field
+    d = B.soar_mx_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0, 0)
+    bad = B.soar_mx_tensor_desc(0x1000, 0, 64, 48, 64, 0x2000, 0x3000, 0, 0)
+    assert B.soar_mxfp4_batch_workspace_bytes([d] * 3, p) == 3 * n and B.soar_mxfp4_batch_workspace_bytes([d] * 20, p) == 8 * n
+    assert B.soar_mxfp4_batch_workspace_bytes([d, bad], p) == 0
+    assert B.soar_mxfp4_quantize_batch([d, bad], p, 0x10000, 1 << 24, 0) == 2
+    assert B.soar_mxfp4_quantize_batch([d, d], p, 0x10000, n, 0) == 5
+    assert B.soar_mxfp4_quantize_batch([], p, 0x10000, 1 << 20, 0) == 0
     assert B.soar_mxfp4_dequantize(0, 0x10, 4, 64, 0, 0x1000, 64, 0) == 1
     assert B.soar_mxfp4_dequantize(0x10, 0x10, 4, 48, 0, 0x1000, 48, 0) == 2
     assert B.soar_mxfp4_dequantize(0x18, 0x10, 4, 64, 0, 0x1000, 64, 0) == 7

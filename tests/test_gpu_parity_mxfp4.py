@@ -125,3 +125,28 @@ def test_full_size_tensors_of_the_model_workload_sampled():
         w = synth.make_weight(specs[k], DEV)
         check(w, B.soar_mx_default_params(), f"config 4 tensor {k} ({specs[k].name})")
         check(w, B.soar_mx_default_params(dss=False), f"config 4 tensor {k} plain")
+
+
+def test_batch_entry_point_equals_separate_calls():
+    """19 tensors of two element types (three launches of one type, then one of the other), ragged ones
+    and a zero tensor among them: the batch gives the bytes of separate calls, twice on one workspace."""
+    g = torch.Generator(device="cpu").manual_seed(77)
+    ws_list = [synth.make_weight(s, DEV) for s in synth.workload_specs(4, 8)[:14]]
+    ws_list.append(torch.zeros(8, 64, dtype=torch.bfloat16, device=DEV))
+    ws_list.append((torch.randn(33, 96, generator=g) * 0.3).to(torch.bfloat16).to(DEV))
+    ws_list += [(torch.randn(50, 160, generator=g) * 2.0 ** e).to(DEV) for e in (-30, 0, 40)]
+    for dss in (False, True):
+        p = B.soar_mx_default_params(dss=dss, n_beta=13)
+        outs = [B.mx_new_outputs(w.shape[0], w.shape[1], DEV) for w in ws_list]
+        descs = [B.mx_make_desc(w, o) for w, o in zip(ws_list, outs)]
+        ws = torch.empty(B.soar_mxfp4_batch_workspace_bytes(descs, p), dtype=torch.uint8, device=DEV)
+        for rep in range(2):
+            for o in outs:
+                o.codes.zero_(); o.scales.zero_(); o.sse.fill_(-1.0); o.status.fill_(-1)
+            B.mx_quantize_batch(descs, p, ws)
+            torch.cuda.synchronize()
+            for k, (w, o) in enumerate(zip(ws_list, outs)):
+                ref = oracle.mxfp4_quantize(host_of(w), dss, p.n_beta, p.beta_lo, p.beta_hi, p.radius)
+                assert np.array_equal(o.codes.cpu().numpy(), ref.codes), (dss, rep, k)
+                assert np.array_equal(o.scales.cpu().numpy(), ref.scales), (dss, rep, k)
+                assert float(o.sse.item()) == ref.sse and int(o.status.item()) == 0, (dss, rep, k)
