@@ -75,6 +75,8 @@ def parse_args():
                          "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph (caller's stream only) and time its replays")
     ap.add_argument("--reps", type=int, default=0,
                     help="after the timed region: this many separately timed steps, reported as median and min")
     ap.add_argument("--cold", action="store_true",
@@ -143,8 +145,18 @@ def main():
     descs = [B.make_desc(w, o, a) for w, o, a in zip(weights, outs, amax_in)]
     ws = B.new_batch_workspace(descs, params, dev)
 
-    def step():
+    def enqueue():
         B.quantize_batch(descs, params, ws)
+
+    step = enqueue
+    if args.graph:
+        params.streams = 1                      # one stream: every launch of the step lands in the capture
+        enqueue()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            enqueue()
+        step = graph.replay
 
     # ---- timed region
     for _ in range(args.warmup):
@@ -346,7 +358,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
                    "dss_radius": K, "search": args.search, "entry_point": "soar_quantize_batch",
-                   "input": "bf16, resident in HBM", "algorithm": args.algorithm,
+                   "input": "bf16, resident in HBM", "algorithm": args.algorithm, "hip_graph": bool(args.graph),
                    **({"iters": params.iters, "n_beta": params.n_beta, "beta": [params.beta_lo, params.beta_hi],
                        "dd_mode": "bracket" if params.dd_mode == B.SOAR_DD_BRACKET else "window",
                        "early_stop_rel": params.early_stop_rel,
