@@ -144,3 +144,15 @@ def test_mxfp4_host_side_argument_validation():
     assert B.soar_mxfp4_dequantize(0, 0x10, 4, 64, 0, 0x1000, 64, 0) == 1
     assert B.soar_mxfp4_dequantize(0x10, 0x10, 4, 48, 0, 0x1000, 48, 0) == 2
     assert B.soar_mxfp4_dequantize(0x18, 0x10, 4, 64, 0, 0x1000, 64, 0) == 7
+
+
+def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
+    import subprocess
+    import sys
+    bench = os.path.join(ROOT, "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2"], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and not r.stdout.strip()
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, bench, "--steps", "1"], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+        assert r.returncode == 2 and "no CPU fallback" in r.stderr and not r.stdout.strip()
