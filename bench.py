@@ -77,8 +77,8 @@ def parse_args():
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph (caller's stream only) and time its replays")
-    ap.add_argument("--reps", type=int, default=0,
-                    help="after the timed region: this many separately timed steps, reported as median and min")
+    ap.add_argument("--reps", type=int, default=7,
+                    help="after the timed region: this many separately timed steps, reported as median and min (0 = none)")
     ap.add_argument("--cold", action="store_true",
                     help="with --reps: write a 1 GiB scratch buffer before every repetition (caches hold none of the input)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
