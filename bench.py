@@ -50,9 +50,12 @@ def iter_lane_ops_per_block_beta(ncand):
 def iterated_params(B, args, streams):
     stop = 0.0 if args.no_early_stop else 1e-3
     if args.algorithm == "paper":
-        return B.soar_paper_params(iters=args.iters or None, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
-    method = B.SOAR_METHOD_CJSO_ONLY if args.algorithm == "cjso-only" else B.SOAR_METHOD_DSS_ONLY
-    return B.soar_arm_params(method, iters=args.iters or 15, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
+        p = B.soar_paper_params(iters=args.iters or None, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
+    else:
+        method = B.SOAR_METHOD_CJSO_ONLY if args.algorithm == "cjso-only" else B.SOAR_METHOD_DSS_ONLY
+        p = B.soar_arm_params(method, iters=args.iters or 15, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
+    p.search_mode = B.SOAR_SEARCH_AUTO if args.search == "auto" else B.SOAR_SEARCH_FULL
+    return p
 
 
 def parse_args():

@@ -148,7 +148,11 @@ size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *param
  * each iteration the tensor's error (binary64 adjacent-pair tree over the block
  * errors) is compared with the previous one for the early stop.  With T = 1,
  * beta = {1} and window candidates both paths return the same bytes.
- * search_mode does not apply to the iterated path (all pairs are evaluated).
+ * search_mode on the iterated path: FULL evaluates the error of every pair; AUTO
+ * (grids of 4 to 128 factors) first forms the codes of every factor and evaluates
+ * errors only for the factors at which a block's codes change -- a pair whose codes
+ * equal those of the factor before it has the same errors and can never be strictly
+ * better.  Both return the same bytes.
  *
  * d_w            in   weights, bf16 or fp32 (see conventions)
  * d_codes        out  rows*cols/2 bytes

@@ -884,6 +884,91 @@ __device__ __forceinline__ void joint_search(const float w[16], float alpha, flo
     }
 }
 
+// assign_codes_rcp without the decoded values (codes only)
+template <bool FAST>
+__device__ __forceinline__ void codes_only_rcp(const float w[16], float scale, uint32_t nib[2])
+{
+    const float r = FAST ? rcp_midrange(scale) : 1.0f / scale;
+    float x[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x[j] = w[j] * r;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t v = nib[h];
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 0], x[8 * h + 1], 1.0f, 0);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 2], x[8 * h + 3], 1.0f, 1);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 4], x[8 * h + 5], 1.0f, 2);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[8 * h + 6], x[8 * h + 7], 1.0f, 3);
+        nib[h] = v;
+    }
+}
+
+constexpr int kMaxListBeta = 128;        // longest factor grid the two-pass form of the search handles
+
+// The same joint search in two passes.  Neighbouring factors very often give a block the same 16
+// codes (a quarter of the paper's 101 factors give new ones, on average, on heavy-tailed weights),
+// and a pair whose codes equal those of the factor before it has the same errors and can never be
+// strictly better.  Pass 1 walks all factors, forms the codes only and notes in LDS the factors at
+// which this block's codes change; pass 2 evaluates the errors for the noted factors alone (its
+// trip count is the longest list in the wave).  The result is that of joint_search, pair for pair.
+// list: kMaxListBeta x kWG bytes, entry e of this lane at list[e * kWG + threadIdx.x].
+template <bool FAST>
+__device__ __forceinline__ void joint_search_two_pass(const float w[16], float alpha, float delta_star,
+                                                      const float *s_beta, int n_beta, bool bracket, int c0,
+                                                      int radius, uint8_t *list, float &best_err, int &best_code,
+                                                      uint32_t best_nib[2], float q[16])
+{
+    uint32_t nib[2] = {0u, 0u};
+    uint32_t p0 = 0u, p1 = 0u;
+    int n = 0;
+    for (int kb = 0; kb < n_beta; ++kb) {
+        codes_only_rcp<FAST>(w, alpha * (delta_star * s_beta[kb]), nib);
+        if (kb == 0 || nib[0] != p0 || nib[1] != p1) {
+            list[n * kWG + threadIdx.x] = (uint8_t)kb;
+            ++n;
+        }
+        p0 = nib[0];
+        p1 = nib[1];
+    }
+    float best = __builtin_inff();
+    float best_beta = s_beta[0];
+    const int lo = c0;
+    const int hi = min(lo + 1, (int)kE4M3Max);
+    const float s_lo = alpha * e4m3_value((uint32_t)lo);
+    const float s_hi = alpha * e4m3_value((uint32_t)hi);
+    best_code = c0;
+    for (int j = 0; __builtin_amdgcn_ballot_w64(j < n) != 0ull; ++j) {
+        if (j < n) {
+            const float bk = s_beta[list[j * kWG + threadIdx.x]];
+            assign_codes_rcp<FAST>(w, alpha * (delta_star * bk), nib, q);
+            if (bracket) {
+                const float e_lo = block_error(w, q, s_lo);
+                const float e_hi = block_error(w, q, s_hi);
+                const float m = fminf(fminf(best, e_lo), e_hi);
+                best_beta = (m < best) ? bk : best_beta;
+                best = m;
+            } else {
+                for (int c = 0; c <= 2 * radius; ++c) {
+                    const int o = (c + 1) >> 1;
+                    const int code = (c & 1) ? max(c0 - o, (int)kE4M3Min) : min(c0 + o, (int)kE4M3Max);
+                    const float e = block_error(w, q, alpha * e4m3_value((uint32_t)code));
+                    if (e < best) { best = e; best_beta = bk; best_code = code; }
+                }
+            }
+        }
+    }
+    assign_codes_rcp<FAST>(w, alpha * (delta_star * best_beta), best_nib, q);
+    if (bracket) {
+        const float e_lo = block_error(w, q, s_lo);
+        const float e_hi = block_error(w, q, s_hi);
+        const bool upper = e_hi < e_lo;
+        best_code = upper ? hi : lo;
+        best_err = upper ? e_hi : e_lo;
+    } else {
+        best_err = best;
+    }
+}
+
 // The Eq. 1-2 state of Algorithm 1 (Delta^q = Delta^d = Delta0) for the iterated
 // path: per block the ratio a/b for Eq. 6 and the error of that state; per tensor
 // the sums of Eq. 5 (-> the global scale of iteration 0) and the error before any
@@ -963,12 +1048,16 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
 // is reproducible), the stop flag and the next global scale.
 // A tensor whose stop flag is set is skipped by every later launch.
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_iter(const Batch batch)
 {
     __shared__ double s_wave[3][4];
     __shared__ double s_stack[3][32];
     __shared__ double s_tree[kWG];
-    __shared__ float s_beta[kMaxBeta];
+    // dynamic LDS: the factor table (n_beta floats, rounded up to 256 bytes), then, for the two-pass
+    // search, the change lists (n_beta x kWG bytes)
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    float *s_beta = reinterpret_cast<float *>(s_dyn);
+    uint8_t *s_list = s_dyn + ((size_t)batch.n_beta * 4 + 255) / 256 * 256;
     __shared__ uint32_t s_last;
 
     uint32_t lwg;
@@ -989,6 +1078,7 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
     const bool bracket = batch.dd_mode == SOAR_DD_BRACKET;
     const int radius = batch.radius;
     const bool one_scale = batch.arm == SOAR_METHOD_CJSO_ONLY;
+    const bool two_pass = n_beta >= 4 && n_beta <= kMaxListBeta && !batch.full_search;
     const bool dss_only = batch.arm == SOAR_METHOD_DSS_ONLY;    // rho then always carries -Delta^d: the search centre
 
     TileTree<3> tree{s_wave, s_stack};
@@ -1024,6 +1114,13 @@ __global__ __launch_bounds__(kWG) void k_iter(const Batch batch)
                     const float sd = alpha * e4m3_value((uint32_t)c0);
                     assign_codes(w, sd, best_nib, q);
                     best_err = block_error(w, q, sd);
+                } else if (two_pass) {
+                    if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
+                        joint_search_two_pass<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, s_list,
+                                                    best_err, best_code, best_nib, q);
+                    else
+                        joint_search_two_pass<false>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, s_list,
+                                                     best_err, best_code, best_nib, q);
                 } else if (__builtin_amdgcn_ballot_w64(!mid) == 0ull) {
                     joint_search<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, best_err, best_code,
                                        best_nib, q);
@@ -1602,6 +1699,14 @@ soar_status launch_group(const Batch &b, uint32_t total_wg, int method, hipStrea
     return SOAR_OK;
 }
 
+// dynamic LDS of k_iter (see there); the two-pass condition mirrors the kernel's
+size_t iter_lds_bytes(const Batch &b)
+{
+    size_t bytes = ((size_t)b.n_beta * 4 + 255) / 256 * 256;
+    if (b.n_beta >= 4 && b.n_beta <= kMaxListBeta && !b.full_search) bytes += (size_t)b.n_beta * kWG;
+    return bytes;
+}
+
 // absmax, the Eq. 1-2 state, then one launch per iteration; a tensor that has
 // stopped early (or is degenerate) makes its workgroups of the later launches return at once
 template <int DT>
@@ -1620,7 +1725,7 @@ soar_status launch_group_iter(Batch &b, uint32_t total_wg, int iters, hipStream_
     for (int it = 0; it < iters; ++it) {
         b.iter_t = it;
         ScopedTimer t(SOAR_KERNEL_ITER, st);
-        hipLaunchKernelGGL(k_iter<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        hipLaunchKernelGGL(k_iter<DT>, dim3(total_wg), dim3(kWG), iter_lds_bytes(b), st, b);
         SOAR_LAUNCH_CHECK();
     }
     return SOAR_OK;

@@ -263,3 +263,20 @@ def test_full_model_workload_in_the_bench_configuration_sampled_tensors():
         n = int(o.iters_run.item())
         assert not np.isnan(tr[: n + 1]).any() and np.isnan(tr[n + 1:]).all(), k
         assert tr[n] < tr[0] and float(o.sse.item()) == tr[n], k
+
+
+def test_two_pass_search_equals_the_plain_loop():
+    """search_mode AUTO (codes first, errors only where a block's codes change) against FULL (every factor
+    evaluated): identical bytes, trace and iteration count, for both candidate modes and a long grid."""
+    spec = synth.workload_specs(2, 2)[0]
+    w = synth.make_weight(spec, DEV)
+    for kw in (dict(), dict(dd_mode=B.SOAR_DD_WINDOW, dss_radius=2, n_beta=31), dict(n_beta=128), dict(n_beta=4),
+               dict(n_beta=129)):
+        a = B.soar_paper_params(iters=3, early_stop_rel=0.0, **kw)
+        f = B.soar_paper_params(iters=3, early_stop_rel=0.0, **kw)
+        f.search_mode = B.SOAR_SEARCH_FULL
+        oa, of = B.quantize_iter(w, a), B.quantize_iter(w, f)
+        torch.cuda.synchronize()
+        assert torch.equal(oa.codes, of.codes) and torch.equal(oa.scales, of.scales), kw
+        assert oa.global_scale.item() == of.global_scale.item(), kw
+        assert torch.equal(oa.sse_trace, of.sse_trace), kw
