@@ -263,6 +263,9 @@ typedef struct {
     float    beta_hi;
     int32_t  radius;         /* K, 0 .. 127                                          */
     int32_t  tiles_per_wg;   /* 0 = chosen by the library; a power of two <= 65536   */
+    int32_t  single_pass;    /* 0: the library's fastest exact search (grids of 4-128
+                                factors: codes of every factor first, errors only where a
+                                block's codes change); 1: evaluate every pair.  Same bytes. */
 } soar_mx_params;
 
 /* dss = 1, 101 factors in [0.5, 1.5], K = 1 */

@@ -1202,6 +1202,7 @@ struct MxTask {
     uint32_t *counters;
     double   *part;
     int32_t  dss, n_beta, radius;
+    int32_t  two_pass;       // search: codes of every factor first, errors only where they change
     float    beta_lo, beta_hi;
 };
 
@@ -1281,14 +1282,78 @@ __device__ __forceinline__ void mx_search(const float w[32], int e0, const float
     }
 }
 
+template <bool FAST>
+__device__ __forceinline__ void mx_codes_only(const float w[32], float scale, uint32_t nib[4])
+{
+    const float r = FAST ? rcp_midrange(scale) : 1.0f / scale;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = w[8 * h + j] * r;
+        uint32_t v = nib[h];
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[0], x[1], 1.0f, 0);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[2], x[3], 1.0f, 1);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[4], x[5], 1.0f, 2);
+        v = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(v, x[6], x[7], 1.0f, 3);
+        nib[h] = v;
+    }
+}
+
+// mx_search in two passes, as joint_search_two_pass: codes of every factor first, errors only for the
+// factors at which this block's codes change (list: n_beta x kWG bytes of LDS)
+template <bool FAST>
+__device__ __forceinline__ void mx_search_two_pass(const float w[32], int e0, const float *s_beta, int n_beta,
+                                                   int radius, uint8_t *list, float &best_err, int &best_code,
+                                                   uint32_t best_nib[4], float q[32])
+{
+    const float x0 = e8m0_value(e0);
+    uint32_t nib[4] = {0u, 0u, 0u, 0u};
+    uint32_t p[4] = {0u, 0u, 0u, 0u};
+    int n = 0;
+    for (int kb = 0; kb < n_beta; ++kb) {
+        mx_codes_only<FAST>(w, x0 * s_beta[kb], nib);
+        if (kb == 0 || nib[0] != p[0] || nib[1] != p[1] || nib[2] != p[2] || nib[3] != p[3]) {
+            list[n * kWG + threadIdx.x] = (uint8_t)kb;
+            ++n;
+        }
+#pragma unroll
+        for (int h = 0; h < 4; ++h) p[h] = nib[h];
+    }
+    float best = __builtin_inff();
+    float best_beta = s_beta[0];
+    for (int j = 0; __builtin_amdgcn_ballot_w64(j < n) != 0ull; ++j) {
+        if (j < n) {
+            const float bk = s_beta[list[j * kWG + threadIdx.x]];
+            mx_assign<FAST>(w, x0 * bk, nib, q);
+            float m = mx_block_error(w, q, x0);
+            for (int c = 1; c <= 2 * radius; ++c) m = fminf(m, mx_block_error(w, q, e8m0_value(mx_candidate(e0, c))));
+            best_beta = (m < best) ? bk : best_beta;
+            best = fminf(best, m);
+        }
+    }
+    best_nib[0] = best_nib[1] = best_nib[2] = best_nib[3] = 0u;
+    mx_assign<FAST>(w, x0 * best_beta, best_nib, q);
+    best_code = e0;
+    best_err = mx_block_error(w, q, x0);
+    for (int c = 1; c <= 2 * radius; ++c) {
+        const int code = mx_candidate(e0, c);
+        const float e = mx_block_error(w, q, e8m0_value(code));
+        if (e < best_err) { best_err = e; best_code = code; }
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
 {
     __shared__ double s_wave[1][4];
     __shared__ double s_stack[1][32];
     __shared__ double s_tree[kWG];
-    __shared__ float s_beta[kMaxBeta];
     __shared__ uint32_t s_last;
+    // dynamic LDS: the factor table (rounded up to 256 bytes), then the change lists of the two-pass search
+    extern __shared__ __align__(16) unsigned char s_dyn_mx[];
+    float *s_beta = reinterpret_cast<float *>(s_dyn_mx);
+    uint8_t *s_list = s_dyn_mx + ((size_t)batch.t[0].n_beta * 4 + 255) / 256 * 256;
 
     const uint32_t tid = threadIdx.x;
     uint32_t which = 0;
@@ -1338,10 +1403,14 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
                 // the reciprocal shortcut needs the scales X0 beta_k to stay within biased exponents [1, 252]
                 const float s_first = e8m0_value(e0) * s_beta[0], s_final = e8m0_value(e0) * s_beta[n_beta - 1];
                 const bool mid = ((__float_as_uint(s_first) >> 23) - 2u) < 250u && ((__float_as_uint(s_final) >> 23) - 2u) < 250u;
-                if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
-                    mx_search<true>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
-                else
-                    mx_search<false>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
+                const bool fast = __builtin_amdgcn_ballot_w64(!mid) == 0ull;
+                if (t.two_pass) {
+                    if (fast) mx_search_two_pass<true>(w, e0, s_beta, n_beta, t.radius, s_list, err, code, nib, q);
+                    else mx_search_two_pass<false>(w, e0, s_beta, n_beta, t.radius, s_list, err, code, nib, q);
+                } else {
+                    if (fast) mx_search<true>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
+                    else mx_search<false>(w, e0, s_beta, n_beta, t.radius, err, code, nib, q);
+                }
             }
             term[0] = (double)err;
             u32x4 packed = {nib[0], nib[1], nib[2], nib[3]};
@@ -1852,6 +1921,7 @@ bool valid_mx_params(const soar_mx_params *p)
     if (!(p->beta_lo > 0.0f) || !(p->beta_hi >= p->beta_lo) || !(p->beta_hi < 1e30f)) return false;
     if (p->radius < 0 || p->radius > 127) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    if (p->single_pass != 0 && p->single_pass != 1) return false;
     return true;
 }
 
@@ -2024,6 +2094,7 @@ void soar_mx_default_params(soar_mx_params *p)
     p->beta_hi = 1.5f;
     p->radius = 1;
     p->tiles_per_wg = 0;
+    p->single_pass = 0;
 }
 
 size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_params *params)
@@ -2059,6 +2130,8 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
         hipLaunchKernelGGL(k_init, dim3(slots * kInitSplit), dim3(kWG), 0, st, base);
         SOAR_LAUNCH_CHECK();
     }
+    const bool two_pass = params->dss && params->single_pass == 0 && params->n_beta >= 4 && params->n_beta <= kMaxListBeta;
+    const size_t lds = ((size_t)params->n_beta * 4 + 255) / 256 * 256 + (two_pass ? (size_t)params->n_beta * kWG : 0);
     // consecutive tensors of one element type share a launch (up to kGroupMax); every kernel leaves the
     // control words of its slots as it found them, so the next group reuses them
     for (int32_t i = 0; i < n;) {
@@ -2099,10 +2172,11 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
             t.radius = params->radius;
             t.beta_lo = params->beta_lo;
             t.beta_hi = params->beta_hi;
+            t.two_pass = two_pass ? 1 : 0;
         }
         ScopedTimer tm(SOAR_KERNEL_MX, st);
-        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), 0, st, b);
-        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), 0, st, b);
+        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), lds, st, b);
+        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), lds, st, b);
         SOAR_LAUNCH_CHECK();
         i = j;
     }

@@ -150,3 +150,13 @@ def test_batch_entry_point_equals_separate_calls():
                 assert np.array_equal(o.codes.cpu().numpy(), ref.codes), (dss, rep, k)
                 assert np.array_equal(o.scales.cpu().numpy(), ref.scales), (dss, rep, k)
                 assert float(o.sse.item()) == ref.sse and int(o.status.item()) == 0, (dss, rep, k)
+
+
+def test_two_pass_search_equals_the_single_pass():
+    spec = synth.workload_specs(2, 2)[0]
+    w = synth.make_weight(spec, DEV)
+    for kw in (dict(), dict(n_beta=128, radius=2), dict(n_beta=4), dict(n_beta=129), dict(n_beta=31, radius=0)):
+        a = B.mx_quantize(w, B.soar_mx_default_params(**kw))
+        b = B.mx_quantize(w, B.soar_mx_default_params(single_pass=True, **kw))
+        torch.cuda.synchronize()
+        assert torch.equal(a.codes, b.codes) and torch.equal(a.scales, b.scales) and a.sse.item() == b.sse.item(), kw
