@@ -7,7 +7,8 @@ the workload, enqueued through the C-ABI batch entry point with the weights
 already resident in HBM.  Default workload: the 36-layer 8B-class decoder
 (252 bf16 tensors, 6.95e9 weights, search radius 4).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (GB/s of bf16 input), ms_per_step, the roofline of the dominant
+kernel, the per-kernel times and the oracle timed on the host cores.
 """
 from __future__ import annotations
 
