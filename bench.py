@@ -79,6 +79,8 @@ def parse_args():
                          "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
+    ap.add_argument("--dtype", choices=["bf16", "fp32"], default="bf16",
+                    help="element type of the weights (NVFP4 algorithms only; every byte figure scales with it)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph (caller's stream only) and time its replays")
     ap.add_argument("--reps", type=int, default=7,
@@ -108,6 +110,9 @@ def main():
     B.lib()
 
     if args.algorithm in ("mxfp4", "mxfp4-dss"):
+        if args.dtype != "bf16":
+            print("bench.py: --dtype fp32 is wired for the NVFP4 algorithms only", file=sys.stderr)
+            sys.exit(2)
         return bench_mxfp4(args, torch, B, synth, dev)
 
     specs = synth.workload_specs(args.workload)
@@ -121,7 +126,7 @@ def main():
     t0 = time.time()
     weights, outs = [], []
     for s in specs:
-        w = synth.make_weight(s, dev)
+        w = synth.make_weight(s, dev, torch.float32 if args.dtype == "fp32" else torch.bfloat16)
         weights.append(w)
         outs.append(B.Quantized(torch.empty((s.rows, s.cols // 2), dtype=torch.uint8, device=dev),
                                 torch.empty((s.rows, s.cols // 16), dtype=torch.uint8, device=dev),
@@ -131,6 +136,10 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
     E = sum(s.numel for s in specs)
+    es = 4.0 if args.dtype == "fp32" else 2.0                       # bytes per weight read
+    BYTES_ABSMAX = BYTES_STATS = es
+    BYTES_SEARCH = es + 0.5625
+    BYTES_3PASS = 3.0 * es + 0.5625
     paper = args.algorithm in ("paper", "cjso-only", "dss-only")      # the iterated path
     rtn_amax = args.algorithm in ("rtn", "rtn-amax")                  # plain NVFP4
     amax_in = [None] * len(specs)
@@ -176,7 +185,7 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall0) * 1e3
     ms_per_step = e0.elapsed_time(e1) / args.steps
-    gbs_in = 2.0 * E / (ms_per_step * 1e-3) / 1e9
+    gbs_in = es * E / (ms_per_step * 1e-3) / 1e9
 
     per_tensor_sse = [float(o.sse.item()) for o in outs]
     sse_soar = sum(per_tensor_sse)
@@ -199,9 +208,9 @@ def main():
         times.sort()
         med = times[len(times) // 2]
         reps = {"n": args.reps, "cold": bool(args.cold), "median_ms": med, "min_ms": times[0],
-                "median_GBps_bf16_in": 2.0 * E / (med * 1e-3) / 1e9,
+                "median_GBps_in": es * E / (med * 1e-3) / 1e9,
                 "median_hbm_frac": (BYTES_SEARCH if args.algorithm == "rtn-amax" else
-                                    4.5625 if args.algorithm == "rtn" else BYTES_3PASS) * E / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
+                                    2.0 * es + 0.5625 if args.algorithm == "rtn" else BYTES_3PASS) * E / (med * 1e-3) / 1e9 / HBM_PEAK_GBS
                 if not paper else None}
 
     # ---- per-kernel durations: HIP events around every launch, on the stream it is
@@ -270,9 +279,9 @@ def main():
             kernels = {k: v for k, v in kernels.items() if v["launches"]}
         achieved = kernels[dom]["GBps"]
         traffic = None
-        if dom == "search" and args.workload == 4 and not args.layers and not rtn_amax:
+        if dom == "search" and args.workload == 4 and not args.layers and not rtn_amax and args.dtype == "bf16":
             traffic = SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
-        if args.algorithm == "rtn-amax" and args.workload == 4 and not args.layers:
+        if args.algorithm == "rtn-amax" and args.workload == 4 and not args.layers and args.dtype == "bf16":
             traffic = RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
         roofline = {"kernel": "k_" + dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -299,7 +308,8 @@ def main():
         sample = specs[: 2 * per_layer] if args.workload in (4, 5) else specs[:1]
         if args.workload == 5:
             sample = specs[:1]
-        host = [w.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) for w in weights[: len(sample)]]
+        host = [w.cpu().contiguous().numpy() if args.dtype == "fp32" else
+                w.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) for w in weights[: len(sample)]]
         n_el = sum(s.numel for s in sample)
         t1 = time.perf_counter()
         if paper:
@@ -339,7 +349,7 @@ def main():
             oracle.quantize(piece, oracle.METHOD_SOAR, K)
         ns1 = (time.perf_counter() - t2) * 1e9 / piece.size
         oracle.set_threads(nthreads)
-        cpu = {"value": 2.0 * n_el / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(),
+        cpu = {"value": es * n_el / dt / 1e9, "unit": f"GB/s {args.dtype} in", "cores": oracle.threads(),
                "single_thread_ns_per_weight": ns1,
                "single_thread_note": "one iteration" if paper else "whole path",
                "kind": "oracle", "seconds": dt, "weights_per_s": n_el / dt,
@@ -350,7 +360,7 @@ def main():
                    "cjso-only": "nvfp4_cjso_only_throughput", "dss-only": "nvfp4_dss_only_throughput",
                    "rtn": "nvfp4_rtn_throughput", "rtn-amax": "nvfp4_rtn_supplied_amax_throughput"}[args.algorithm],
         "value": gbs_in,
-        "unit": "GB/s bf16 in",
+        "unit": f"GB/s {args.dtype} in",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -362,7 +372,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
                    "dss_radius": K, "search": args.search, "entry_point": "soar_quantize_batch",
-                   "input": "bf16, resident in HBM", "algorithm": args.algorithm, "hip_graph": bool(args.graph),
+                   "input": f"{args.dtype}, resident in HBM", "algorithm": args.algorithm, "hip_graph": bool(args.graph),
                    **({"iters": params.iters, "n_beta": params.n_beta, "beta": [params.beta_lo, params.beta_hi],
                        "dd_mode": "bracket" if params.dd_mode == B.SOAR_DD_BRACKET else "window",
                        "early_stop_rel": params.early_stop_rel,
