@@ -384,6 +384,27 @@ def test_tensor_wide_sums_follow_the_zero_padded_pair_tree(rows, cols):
     assert math.isclose(tr["N"], math.fsum(tn), rel_tol=1e-13)
 
 
+def test_row_shards_of_aligned_power_of_two_size_reproduce_the_tree():
+    """What sharding a tensor by rows would rely on: if every shard holds an aligned power-of-two range of
+    blocks, the tree over the shards' own tree sums is the tree over all blocks, bit for bit; the global
+    scale of the whole tensor then follows from the shards' maxima and (N, M) pairs alone."""
+    rng = np.random.default_rng(11)
+    f = (rng.standard_t(3, size=(64, 256)) * np.exp(rng.uniform(-2, 2, size=(64, 1))) * 0.02).astype(np.float32)
+    whole = oracle.quantize(f, oracle.METHOD_SOAR, 2, want_trace=True)
+    tr = whole.trace
+    d0 = E4M3[tr["code0"]]
+    tn = [float(a) * float(d) for a, d in zip(tr["a"], d0)]
+    tm = [float(b) * float(d) * float(d) for b, d in zip(tr["b"], d0)]
+    for shards in (2, 4, 8):
+        n = len(tn) // shards                      # 1024 blocks: every shard an aligned power of two
+        part_n = [_padded_tree(tn[k * n:(k + 1) * n]) for k in range(shards)]
+        part_m = [_padded_tree(tm[k * n:(k + 1) * n]) for k in range(shards)]
+        assert _padded_tree(part_n) == tr["N"] and _padded_tree(part_m) == tr["M"]
+        assert np.float32(_padded_tree(part_n) / _padded_tree(part_m)) == tr["alpha1"]
+    amax = max(float(np.abs(f[k * 16:(k + 1) * 16]).max()) for k in range(4))
+    assert np.float32(np.float32(amax) / np.float32(2688.0)) == tr["alpha0"]
+
+
 # --------------------------------------------------------------- degenerate inputs
 def test_all_zero_and_non_finite_tensors():
     z = np.zeros((4, 32), dtype=np.uint16)
