@@ -423,6 +423,28 @@ def quantize_rtn_amax(w: torch.Tensor, amax_in: torch.Tensor, workspace: Optiona
     return out
 
 
+def quantize_tensors(weights: Sequence[torch.Tensor], params: Optional[soar_params] = None,
+                     workspace: Optional[torch.Tensor] = None) -> list:
+    """The linear layers of a model in one soar_quantize_batch call: allocates the outputs (with the
+    trace buffers when the parameters select the iterated path), one shared workspace, and enqueues
+    everything on the current stream.  Returns one Quantized per tensor, in order."""
+    if not weights:
+        return []
+    if params is None:
+        params = soar_default_params()
+    iterated = (params.iters != 1 or params.n_beta != 1 or params.beta_lo != 1.0 or
+                params.dd_mode != SOAR_DD_WINDOW or params.method in (SOAR_METHOD_CJSO_ONLY, SOAR_METHOD_DSS_ONLY))
+    outs = []
+    for w in weights:
+        rows, cols, _ = _check_matrix(w)
+        outs.append(new_outputs(rows, cols, w.device, params.iters if iterated else 0))
+    descs = [make_desc(w, o) for w, o in zip(weights, outs)]
+    if workspace is None:
+        workspace = new_batch_workspace(descs, params, weights[0].device)
+    quantize_batch(descs, params, workspace)
+    return outs
+
+
 def dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:
     rows, cols = q.scales.shape[0], q.scales.shape[1] * 16
     out = torch.empty((rows, cols), dtype=out_dtype, device=q.codes.device)

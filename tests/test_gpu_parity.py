@@ -331,3 +331,20 @@ def test_70b_class_all_layers_full_size():
     for layer in range(4, 80, 4):
         print(f"layers {layer}..{layer + 3}", flush=True)
         _run_70b_layers(layer, 4)
+
+
+def test_quantize_tensors_helper_equals_separate_calls():
+    specs = synth.workload_specs(4, 8)[:9]
+    weights = [synth.make_weight(s, DEV) for s in specs]
+    outs = B.quantize_tensors(weights)
+    full = B.quantize_tensors(weights, B.soar_paper_params(iters=3, n_beta=9))
+    torch.cuda.synchronize()
+    for w, o, f in zip(weights, outs, full):
+        one = B.quantize(w)
+        it = B.quantize_iter(w, B.soar_paper_params(iters=3, n_beta=9))
+        torch.cuda.synchronize()
+        assert torch.equal(o.codes, one.codes) and torch.equal(o.scales, one.scales)
+        assert o.global_scale.item() == one.global_scale.item()
+        assert torch.equal(f.codes, it.codes) and torch.equal(f.scales, it.scales)
+        assert f.iters_run.item() == it.iters_run.item() and f.sse.item() == it.sse.item()
+    assert B.quantize_tensors([]) == []
