@@ -157,3 +157,12 @@ def test_bench_refuses_more_than_one_gpu_and_a_missing_gpu():
     if not torch.cuda.is_available():
         r = subprocess.run([sys.executable, bench, "--steps", "1"], stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
         assert r.returncode == 2 and "no CPU fallback" in r.stderr and not r.stdout.strip()
+
+
+def test_missing_library_raises_instead_of_falling_back(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "paper_2605_12245_amd", "no_such_library.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+    with pytest.raises(RuntimeError):
+        B.soar_default_params()
