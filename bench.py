@@ -402,7 +402,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
     if args.layers and args.workload in (4, 5):
         specs = specs[: args.layers * per_layer]
     dss = args.algorithm == "mxfp4-dss"
-    p = B.soar_mx_default_params(dss=dss, tiles_per_wg=args.tpw)
+    p = B.soar_mx_default_params(dss=dss, tiles_per_wg=args.tpw, streams=args.streams)
     weights = [synth.make_weight(s, dev) for s in specs]
     outs = [B.mx_new_outputs(s.rows, s.cols, dev) for s in specs]
     descs = [B.mx_make_desc(w, o) for w, o in zip(weights, outs)]

@@ -266,6 +266,9 @@ typedef struct {
     int32_t  single_pass;    /* 0: the library's fastest exact search (grids of 4-128
                                 factors: codes of every factor first, errors only where a
                                 block's codes change); 1: evaluate every pair.  Same bytes. */
+    int32_t  streams;        /* soar_mxfp4_quantize_batch: 0 = launch groups alternate between
+                                the caller's stream and one internal stream (forked and joined
+                                by events); 1 = everything on the caller's stream            */
 } soar_mx_params;
 
 /* dss = 1, 101 factors in [0.5, 1.5], K = 1 */

@@ -60,6 +60,7 @@ class soar_mx_params(C.Structure):
     _fields_ = [
         ("struct_size", C.c_uint32), ("dss", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float),
         ("beta_hi", C.c_float), ("radius", C.c_int32), ("tiles_per_wg", C.c_int32), ("single_pass", C.c_int32),
+        ("streams", C.c_int32),
     ]
 
 
@@ -238,7 +239,7 @@ def soar_e4m3_project_f32(d_x, n, d_out, hip_stream) -> int:
 
 def soar_mx_default_params(dss: bool = True, n_beta: Optional[int] = None, beta_lo: Optional[float] = None,
                            beta_hi: Optional[float] = None, radius: Optional[int] = None,
-                           tiles_per_wg: int = 0, single_pass: bool = False) -> soar_mx_params:
+                           tiles_per_wg: int = 0, single_pass: bool = False, streams: int = 0) -> soar_mx_params:
     p = soar_mx_params()
     lib().soar_mx_default_params(C.byref(p))
     p.dss = 1 if dss else 0
@@ -247,6 +248,7 @@ def soar_mx_default_params(dss: bool = True, n_beta: Optional[int] = None, beta_
             setattr(p, name, v)
     p.tiles_per_wg = tiles_per_wg
     p.single_pass = 1 if single_pass else 0
+    p.streams = streams
     return p
 
 

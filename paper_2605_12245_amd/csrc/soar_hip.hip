@@ -1922,6 +1922,7 @@ bool valid_mx_params(const soar_mx_params *p)
     if (p->radius < 0 || p->radius > 127) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
     if (p->single_pass != 0 && p->single_pass != 1) return false;
+    if (p->streams < 0 || p->streams > kLanes) return false;
     return true;
 }
 
@@ -2095,12 +2096,27 @@ void soar_mx_default_params(soar_mx_params *p)
     p->radius = 1;
     p->tiles_per_wg = 0;
     p->single_pass = 0;
+    p->streams = 0;
 }
 
 size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_params *params)
 {
     if (!valid_mx_params(params) || check_mx_shape(rows, cols, cols) != SOAR_OK) return 0;
     return kSlotBytes;
+}
+
+static int32_t mx_group_end(int32_t n, const soar_mx_tensor_desc *descs, int32_t i)
+{
+    int32_t j = i + 1;
+    while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype) ++j;
+    return j;
+}
+
+static int32_t mx_group_count(int32_t n, const soar_mx_tensor_desc *descs)
+{
+    int32_t groups = 0;
+    for (int32_t i = 0; i < n; i = mx_group_end(n, descs, i)) ++groups;
+    return groups;
 }
 
 soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *descs, const soar_mx_params *params,
@@ -2122,21 +2138,45 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
     if (n == 0) return SOAR_OK;
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
     const int32_t slots = n < kGroupMax ? n : kGroupMax;
-    if (workspace_bytes < (size_t)slots * kSlotBytes) return SOAR_ERR_WORKSPACE;
+    const int32_t groups = mx_group_count(n, descs);
+    const int ws_lanes = groups > 1 ? kLanes : 1;
+    if (workspace_bytes < (size_t)ws_lanes * slots * kSlotBytes) return SOAR_ERR_WORKSPACE;
+    const int lanes = (groups > 1 && params->streams != 1) ? kLanes : 1;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *base = static_cast<char *>(d_workspace);
+    // launch groups alternate between the caller's stream and one internal stream (forked and joined with
+    // events), each with its own control slots, so that the ramp and the tail of one launch overlap another
+    hipStream_t lane_stream[kLanes] = {st, st};
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    if (lanes > 1) {
+        lane_stream[1] = aux_stream();
+        if (!lane_stream[1]) return SOAR_ERR_HIP;
+        if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return SOAR_ERR_HIP;
+        if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
+            (void)hipEventDestroy(ev_fork);
+            return SOAR_ERR_HIP;
+        }
+    }
+    soar_status result = SOAR_OK;
     {
         ScopedTimer tm(SOAR_KERNEL_INIT, st);
-        hipLaunchKernelGGL(k_init, dim3(slots * kInitSplit), dim3(kWG), 0, st, base);
-        SOAR_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_init, dim3(lanes * slots * kInitSplit), dim3(kWG), 0, st, base);
+        if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
+    }
+    if (lanes > 1 && result == SOAR_OK) {
+        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(lane_stream[1], ev_fork, 0) != hipSuccess)
+            result = SOAR_ERR_HIP;
     }
     const bool two_pass = params->dss && params->single_pass == 0 && params->n_beta >= 4 && params->n_beta <= kMaxListBeta;
     const size_t lds = ((size_t)params->n_beta * 4 + 255) / 256 * 256 + (two_pass ? (size_t)params->n_beta * kWG : 0);
     // consecutive tensors of one element type share a launch (up to kGroupMax); every kernel leaves the
     // control words of its slots as it found them, so the next group reuses them
-    for (int32_t i = 0; i < n;) {
-        int32_t j = i + 1;
-        while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype) ++j;
+    int32_t g = 0;
+    for (int32_t i = 0; i < n && result == SOAR_OK; ++g) {
+        const int32_t j = mx_group_end(n, descs, i);
+        const int lane = g % lanes;
+        char *lane_base = base + (size_t)lane * slots * kSlotBytes;
+        hipStream_t lst = lane_stream[lane];
         MxBatch b;
         std::memset(&b, 0, sizeof(b));
         b.n = (uint32_t)(j - i);
@@ -2163,7 +2203,7 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
             t.n_wg = (tiles + tpw - 1) / tpw;
             t.wg_begin = wg;
             wg += t.n_wg;
-            char *slot = base + (size_t)(k - i) * kSlotBytes;
+            char *slot = lane_base + (size_t)(k - i) * kSlotBytes;
             t.ctrl = reinterpret_cast<Ctrl *>(slot);
             t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
             t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
@@ -2174,13 +2214,20 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
             t.beta_hi = params->beta_hi;
             t.two_pass = two_pass ? 1 : 0;
         }
-        ScopedTimer tm(SOAR_KERNEL_MX, st);
-        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), lds, st, b);
-        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), lds, st, b);
-        SOAR_LAUNCH_CHECK();
+        ScopedTimer tm(SOAR_KERNEL_MX, lst);
+        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), lds, lst, b);
+        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), lds, lst, b);
+        if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
         i = j;
     }
-    return SOAR_OK;
+    if (lanes > 1) {
+        // always join, also after a failed launch, so that the caller's stream stays ordered
+        if (hipEventRecord(ev_join, lane_stream[1]) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess)
+            result = SOAR_ERR_HIP;
+        (void)hipEventDestroy(ev_fork);
+        (void)hipEventDestroy(ev_join);
+    }
+    return result;
 }
 
 size_t soar_mxfp4_batch_workspace_bytes(int32_t n, const soar_mx_tensor_desc *descs, const soar_mx_params *params)
@@ -2188,7 +2235,7 @@ size_t soar_mxfp4_batch_workspace_bytes(int32_t n, const soar_mx_tensor_desc *de
     if (n <= 0 || !descs || !valid_mx_params(params)) return 0;
     for (int32_t k = 0; k < n; ++k)
         if (check_mx_shape(descs[k].rows, descs[k].cols, descs[k].ld_elems) != SOAR_OK) return 0;
-    return (size_t)(n < kGroupMax ? n : kGroupMax) * kSlotBytes;
+    return (size_t)(mx_group_count(n, descs) > 1 ? kLanes : 1) * (size_t)(n < kGroupMax ? n : kGroupMax) * kSlotBytes;
 }
 
 soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,

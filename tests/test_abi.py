@@ -130,14 +130,14 @@ def test_mxfp4_host_side_argument_validation():
     assert q(p, d_w=0x1004) == 7 and q(p, codes=0x2008) == 7 and q(p, ld=68) == 7
     assert q(p, ws=0) == 5 and q(p, ws=0x10010) == 5 and q(p, ws_bytes=64) == 5
     for field, bad in (("dss", 2), ("n_beta", 0), ("n_beta", 5000), ("beta_lo", 0.0), ("beta_hi", 0.25),
-                       ("radius", -1), ("radius", 128), ("tiles_per_wg", 3), ("single_pass", 2),
+                       ("radius", -1), ("radius", 128), ("tiles_per_wg", 3), ("single_pass", 2), ("streams", 3),
                        ("struct_size", 8)):
         r = B.soar_mx_default_params()
         setattr(r, field, bad)
         assert q(r) == 4, field
     d = B.soar_mx_tensor_desc(0x1000, 0, 64, 64, 64, 0x2000, 0x3000, 0, 0)
     bad = B.soar_mx_tensor_desc(0x1000, 0, 64, 48, 64, 0x2000, 0x3000, 0, 0)
-    assert B.soar_mxfp4_batch_workspace_bytes([d] * 3, p) == 3 * n and B.soar_mxfp4_batch_workspace_bytes([d] * 20, p) == 8 * n
+    assert B.soar_mxfp4_batch_workspace_bytes([d] * 3, p) == 3 * n and B.soar_mxfp4_batch_workspace_bytes([d] * 20, p) == 2 * 8 * n
     assert B.soar_mxfp4_batch_workspace_bytes([d, bad], p) == 0
     assert B.soar_mxfp4_quantize_batch([d, bad], p, 0x10000, 1 << 24, 0) == 2
     assert B.soar_mxfp4_quantize_batch([d, d], p, 0x10000, n, 0) == 5

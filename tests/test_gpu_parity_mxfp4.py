@@ -135,8 +135,8 @@ def test_batch_entry_point_equals_separate_calls():
     ws_list.append(torch.zeros(8, 64, dtype=torch.bfloat16, device=DEV))
     ws_list.append((torch.randn(33, 96, generator=g) * 0.3).to(torch.bfloat16).to(DEV))
     ws_list += [(torch.randn(50, 160, generator=g) * 2.0 ** e).to(DEV) for e in (-30, 0, 40)]
-    for dss in (False, True):
-        p = B.soar_mx_default_params(dss=dss, n_beta=13)
+    for dss, streams in ((False, 0), (True, 0), (True, 1)):
+        p = B.soar_mx_default_params(dss=dss, n_beta=13, streams=streams)
         outs = [B.mx_new_outputs(w.shape[0], w.shape[1], DEV) for w in ws_list]
         descs = [B.mx_make_desc(w, o) for w, o in zip(ws_list, outs)]
         ws = torch.empty(B.soar_mxfp4_batch_workspace_bytes(descs, p), dtype=torch.uint8, device=DEV)
