@@ -429,9 +429,10 @@ def bench_mxfp4(args, torch, B, synth, dev):
     kernels, roofline = {}, None
     if not args.no_kernel_timing:
         n_prof = min(args.steps, 2 if dss else 5)
+        p_one = B.soar_mx_default_params(dss=dss, tiles_per_wg=args.tpw, streams=1)     # launches must not overlap
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
-            step()
+            step(p_one)
         torch.cuda.synchronize()
         for kid, nm in ((B.SOAR_KERNEL_INIT, "init"), (B.SOAR_KERNEL_MX, "mx")):
             ms, n = B.soar_kernel_timing_read(kid)
@@ -445,7 +446,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
             roofline = {"kernel": "k_mx", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
                         "flops_per_block_and_factor": 32 + 32 + 32 + ncand * 128,
-                        "note": "all k_mx launches of a step together; HIP-event durations on the launch stream"}
+                        "note": "all k_mx launches of a step together; HIP-event durations on the launch stream, single-stream pass"}
         else:
             per_w = 2.0 + 0.5 + 1.0 / 32.0
             gbs = per_w * E / t_mx / 1e9
@@ -453,7 +454,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
                         "weights_per_launch": E / (kernels["mx"]["launches"] / n_prof),
                         "avg_launch_us": kernels["mx"]["avg_us"],
-                        "note": "per-launch HIP-event durations on the launch stream, up to 8 tensors per launch"}
+                        "note": "per-launch HIP-event durations on the launch stream, single-stream pass, up to 8 tensors per launch"}
 
     # error of the plain conversion, for the ratio the paper's table is about
     p_plain = B.soar_mx_default_params(dss=False)
