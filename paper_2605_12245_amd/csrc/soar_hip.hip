@@ -191,6 +191,66 @@ __device__ __forceinline__ void load_block(const void *base, size_t elem_off, fl
     }
 }
 
+// 16-byte pieces of one block of NELEM elements
+template <int DT, int NELEM>
+constexpr int pieces_per_block() { return NELEM * (DT == SOAR_BF16 ? 2 : 4) / 16; }
+
+// The 64 consecutive blocks of a wave lie in one contiguous range when the rows of the tensor are
+// packed (ld == cols).  The wave reads that range in fully coalesced 16-byte pieces (lane l takes
+// pieces l, l + 64, ...: a lane that reads its own 32, 64 or 128 contiguous bytes touches every cache
+// line of the range with every load instruction instead), then each lane picks the pieces of its own
+// block out of a wave-private LDS region of 64 * P pieces.  Inside a block's slots the pieces are
+// rotated by the block's row of 256 bytes, so that neither side has bank conflicts.  Data movement
+// only: w[] ends up exactly as load_block leaves it.  Blocks at or beyond nblk read as zeros.
+// The wave's LDS operations execute in order, so the exchange needs no workgroup barrier.
+template <int DT, int NELEM, bool STREAM>
+__device__ __forceinline__ void load_wave_blocks(const void *base, uint32_t wave_first, uint32_t nblk,
+                                                 u32x4 *s_wave, float w[NELEM])
+{
+    constexpr int P = pieces_per_block<DT, NELEM>();
+    constexpr uint32_t kPerRow = 16 / P;                 // blocks per 256 bytes of LDS
+    static_assert(P == 2 || P == 4 || P == 8, "block of 32, 64 or 128 bytes");
+    const uint32_t lane = threadIdx.x & 63u;
+    const u32x4 *g = static_cast<const u32x4 *>(base) + (size_t)wave_first * P;
+    const uint32_t have = wave_first < nblk ? min(64u, nblk - wave_first) * (uint32_t)P : 0u;
+    u32x4 v[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint32_t idx = (uint32_t)p * 64u + lane;
+        v[p] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < have) v[p] = load16<STREAM>(g + idx);
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint32_t idx = (uint32_t)p * 64u + lane;
+        const uint32_t u = idx / (uint32_t)P, piece = idx % (uint32_t)P;
+        s_wave[u * P + ((piece + u / kPerRow) & (uint32_t)(P - 1))] = v[p];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int p = 0; p < P; ++p) v[p] = s_wave[lane * P + (((uint32_t)p + lane / kPerRow) & (uint32_t)(P - 1))];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();                     // the next exchange writes these slots again
+    if constexpr (DT == SOAR_BF16) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint32_t u[4] = {v[p].x, v[p].y, v[p].z, v[p].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                w[8 * p + 2 * k] = f_of(u[k] << 16);
+                w[8 * p + 2 * k + 1] = f_of(u[k] & 0xFFFF0000u);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            w[4 * p] = f_of(v[p].x); w[4 * p + 1] = f_of(v[p].y); w[4 * p + 2] = f_of(v[p].z); w[4 * p + 3] = f_of(v[p].w);
+        }
+    }
+}
+
 __device__ __forceinline__ size_t block_offset(const Geom &g, uint32_t i)
 {
     if (g.contiguous) return (size_t)i * 16;
@@ -1183,7 +1243,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 // ------------------------------------------------------------------ MXFP4
 // Blocks of 32 elements with an E8M0 scale byte (OCP Microscaling Formats v1.0), plain
 // conversion or with the decoupled scale search of Sec. 3.3 carried over to it (Sec. 4.3,
-// "DSS on MXFP4").  One lane owns one block: four (bf16) or eight (fp32) 128-bit loads.
+// "DSS on MXFP4").  One lane owns one block of 64 (bf16) or 128 (fp32) bytes.
 // There is no tensor-wide scale, so this is a single pass; the only tensor-wide result is the
 // error sum (exact adjacent-pair tree, as in the iterated path).
 struct MxTask {
@@ -1343,13 +1403,15 @@ __device__ __forceinline__ void mx_search_two_pass(const float w[32], int e0, co
     }
 }
 
-template <int DT>
+template <int DT, bool DSS>
 __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
 {
     __shared__ double s_wave[1][4];
     __shared__ double s_stack[1][32];
     __shared__ double s_tree[kWG];
     __shared__ uint32_t s_last;
+    constexpr int kP = pieces_per_block<DT, 32>();
+    __shared__ u32x4 s_x[DSS ? 1 : kWG * kP];          // load_wave_blocks: one region per wave
     // dynamic LDS: the factor table (rounded up to 256 bytes), then the change lists of the two-pass search
     extern __shared__ __align__(16) unsigned char s_dyn_mx[];
     float *s_beta = reinterpret_cast<float *>(s_dyn_mx);
@@ -1361,7 +1423,7 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
         if (blockIdx.x >= batch.t[j].wg_begin) which = j;
     const MxTask t = batch.t[which];
     const uint32_t lwg = blockIdx.x - t.wg_begin;
-    const int n_beta = t.dss ? t.n_beta : 0;
+    const int n_beta = DSS ? t.n_beta : 0;
     for (int k = (int)tid; k < n_beta; k += kWG)
         s_beta[k] = n_beta <= 1 ? t.beta_lo
                                 : (t.beta_lo * (float)(n_beta - 1 - k) + t.beta_hi * (float)k) / (float)(n_beta - 1);
@@ -1373,18 +1435,27 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
     for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
         const uint32_t i = (tile0 + k) * kWG + tid;
         double term[1] = {0.0};
+        float w[32];
+        // the plain conversion is bound by the reads: packed rows go through the coalescing exchange
+        const bool exchanged = !DSS && t.contiguous;
+        if constexpr (!DSS) {
+            if (exchanged) load_wave_blocks<DT, 32, true>(t.w, i - (tid & 63u), t.nblk, s_x + (tid >> 6) * (64 * kP), w);
+        }
         if (i < t.nblk) {
-            float w[32], q[32];
+            float q[32];
             uint32_t nib[4] = {0u, 0u, 0u, 0u};
-            size_t off;
-            if (t.contiguous) {
-                off = (size_t)i * 32;
-            } else {
-                const uint32_t row = i / t.bpr;
-                off = (size_t)row * (size_t)t.ld + (size_t)(i - row * t.bpr) * 32;
+            if (!exchanged) {
+                size_t off;
+                if (t.contiguous) {
+                    off = (size_t)i * 32;
+                } else {
+                    const uint32_t row = i / t.bpr;
+                    off = (size_t)row * (size_t)t.ld + (size_t)(i - row * t.bpr) * 32;
+                }
+                // ordinary loads: a lane's four or eight loads share cache lines, which streaming loads would drop
+                load_block<DT, false>(t.w, off, w);
+                load_block<DT, false>(t.w, off + 16, w + 16);
             }
-            load_block<DT, true>(t.w, off, w);
-            load_block<DT, true>(t.w, off + 16, w + 16);
             uint32_t mbits = 0u;
 #pragma unroll
             for (int j = 0; j < 32; ++j) mbits = max(mbits, __float_as_uint(w[j]) & 0x7FFFFFFFu);
@@ -1395,7 +1466,7 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
             const int e0 = mbits == 0u ? 127 : min(max(ex - 1 - 2, -127), 127) + 127;
             int code = e0;
             float err;
-            if (!t.dss) {
+            if constexpr (!DSS) {
                 const float x0 = e8m0_value(e0);
                 mx_assign<false>(w, x0, nib, q);
                 err = mx_block_error(w, q, x0);
@@ -2215,8 +2286,15 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
             t.two_pass = two_pass ? 1 : 0;
         }
         ScopedTimer tm(SOAR_KERNEL_MX, lst);
-        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx<SOAR_BF16>, dim3(wg), dim3(kWG), lds, lst, b);
-        else hipLaunchKernelGGL(k_mx<SOAR_FP32>, dim3(wg), dim3(kWG), lds, lst, b);
+        // the plain conversion is an instantiation of its own: it needs half the registers of the search
+        const bool bf16 = descs[i].dtype == SOAR_BF16;
+        if (params->dss) {
+            if (bf16) hipLaunchKernelGGL((k_mx<SOAR_BF16, true>), dim3(wg), dim3(kWG), lds, lst, b);
+            else hipLaunchKernelGGL((k_mx<SOAR_FP32, true>), dim3(wg), dim3(kWG), lds, lst, b);
+        } else {
+            if (bf16) hipLaunchKernelGGL((k_mx<SOAR_BF16, false>), dim3(wg), dim3(kWG), lds, lst, b);
+            else hipLaunchKernelGGL((k_mx<SOAR_FP32, false>), dim3(wg), dim3(kWG), lds, lst, b);
+        }
         if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
         i = j;
     }

@@ -64,12 +64,14 @@ def test_ragged_shapes_and_launch_shapes(rows, cols):
     g = torch.Generator(device="cpu").manual_seed(rows * 31 + cols)
     w = (torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g) * 2) * 0.02)
     w = w.to(torch.bfloat16).to(DEV)
-    base, _ = check(w, B.soar_mx_default_params(n_beta=15), f"{rows}x{cols}")
-    for tpw in (2, 8):
-        other = B.mx_quantize(w, B.soar_mx_default_params(n_beta=15, tiles_per_wg=tpw))
-        torch.cuda.synchronize()
-        assert torch.equal(base.codes, other.codes) and torch.equal(base.scales, other.scales)
-        assert base.sse.item() == other.sse.item()
+    # the plain conversion of packed rows reads through the coalescing exchange: both element types, ragged waves
+    for x, dss in ((w, True), (w, False), (w.float() * 1.0009765625, False)):
+        base, _ = check(x, B.soar_mx_default_params(dss=dss, n_beta=15), f"{rows}x{cols} {x.dtype} dss={dss}")
+        for tpw in (2, 8):
+            other = B.mx_quantize(x, B.soar_mx_default_params(dss=dss, n_beta=15, tiles_per_wg=tpw))
+            torch.cuda.synchronize()
+            assert torch.equal(base.codes, other.codes) and torch.equal(base.scales, other.scales)
+            assert base.sse.item() == other.sse.item()
 
 
 def test_fp32_strided_extreme_magnitudes_zero_and_non_finite():
