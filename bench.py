@@ -69,14 +69,16 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
-    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax", "mxfp4", "mxfp4-dss"],
+    ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax", "mxfp4", "mxfp4-dss",
+                                               "dequantize", "recon-error"],
                     default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
                          "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
                          "cjso-only / dss-only: the arms of the paper's component study (T = 15, early stop); "
                          "rtn: plain NVFP4 (two passes); "
                          "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass); "
-                         "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search")
+                         "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search; "
+                         "dequantize / recon-error: Eq. 3 / Eq. 4 on the stored form of every tensor (one call per tensor)")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--dtype", choices=["bf16", "fp32"], default="bf16",
@@ -114,6 +116,9 @@ def main():
             print("bench.py: --dtype fp32 is wired for the NVFP4 algorithms only", file=sys.stderr)
             sys.exit(2)
         return bench_mxfp4(args, torch, B, synth, dev)
+
+    if args.algorithm in ("dequantize", "recon-error"):
+        return bench_stored_form(args, torch, B, synth, dev)
 
     specs = synth.workload_specs(args.workload)
     per_layer = {4: 7, 5: 3}.get(args.workload, 1)
@@ -393,6 +398,107 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def bench_stored_form(args, torch, B, synth, dev):
+    """Eq. 3 (soar_dequantize) or Eq. 4 (soar_recon_error) over every tensor of the workload, one call
+    per tensor on the current stream, on the stored form the single-step path produced."""
+    import numpy as np
+    specs = synth.workload_specs(args.workload)
+    per_layer = {4: 7, 5: 3}.get(args.workload, 1)
+    if args.layers and args.workload in (4, 5):
+        specs = specs[: args.layers * per_layer]
+    deq = args.algorithm == "dequantize"
+    tdt = torch.float32 if args.dtype == "fp32" else torch.bfloat16
+    es = 4.0 if args.dtype == "fp32" else 2.0
+    code = B.SOAR_FP32 if args.dtype == "fp32" else B.SOAR_BF16
+    weights = [synth.make_weight(s, dev, tdt) for s in specs]
+    qs = B.quantize_tensors(weights, B.soar_default_params(B.SOAR_METHOD_SOAR, specs[0].dss_radius))
+    torch.cuda.synchronize()
+    E = sum(s.numel for s in specs)
+    st = torch.cuda.current_stream().cuda_stream
+    if deq:
+        backs = [torch.empty((s.rows, s.cols), dtype=tdt, device=dev) for s in specs]
+
+        def step():
+            for s, q, o in zip(specs, qs, backs):
+                rc = B.soar_dequantize(q.codes.data_ptr(), q.scales.data_ptr(), q.global_scale.data_ptr(), s.rows, s.cols,
+                                       code, o.data_ptr(), s.cols, st)
+                assert rc == B.SOAR_OK, rc
+    else:
+        sses = torch.zeros(len(specs), dtype=torch.float64, device=dev)
+
+        def step():
+            for k, (s, q, w) in enumerate(zip(specs, qs, weights)):
+                rc = B.soar_recon_error(w.data_ptr(), code, s.rows, s.cols, s.cols, q.codes.data_ptr(), q.scales.data_ptr(),
+                                        q.global_scale.data_ptr(), sses.data_ptr() + 8 * k, st)
+                assert rc == B.SOAR_OK, rc
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    per_w = (0.5625 + es) if deq else (es + 0.5625)       # codes + scale bytes, and the weights written or read
+    kid, kname = (B.SOAR_KERNEL_DEQUANT, "k_dequant") if deq else (B.SOAR_KERNEL_RECON, "k_recon")
+    kernels, roofline = {}, None
+    if not args.no_kernel_timing:
+        n_prof = min(args.steps, 5)
+        B.soar_kernel_timing_enable(True)
+        for _ in range(n_prof):
+            step()
+        torch.cuda.synchronize()
+        ms, n = B.soar_kernel_timing_read(kid)
+        B.soar_kernel_timing_enable(False)
+        kernels[kname[2:]] = {"launches": n, "total_ms": ms, "avg_us": ms / n * 1e3, "ms_per_step": ms / n_prof}
+        gbs = per_w * E * n_prof / (ms * 1e-3) / 1e9
+        roofline = {"kernel": kname, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
+                    "weights_per_launch": E / (n / n_prof), "avg_launch_us": ms / n * 1e3,
+                    "note": "per-launch HIP-event durations on the launch stream, one launch per tensor"
+                            + ("" if deq else " (with the one-thread launch that clears the sum)")}
+    extra = {}
+    if not deq:
+        got = float(sses.sum().item())
+        want = sum(float(q.sse.item()) for q in qs)
+        extra["sse_recon"] = got
+        extra["sse_from_quantize"] = want
+        extra["sse_rel_diff"] = abs(got - want) / want if want > 0 else 0.0
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        k = 4 if len(specs) > 4 else 0
+        q = qs[k]
+        c, sc, a = q.codes.cpu().numpy(), q.scales.cpu().numpy(), float(q.global_scale.item())
+        h = weights[k].cpu().contiguous()
+        h = h.numpy() if args.dtype == "fp32" else h.view(torch.int16).numpy().view(np.uint16)
+        reps = 0
+        t1 = time.perf_counter()
+        while time.perf_counter() - t1 < 10.0:
+            if deq:
+                oracle.dequantize(c, sc, a, oracle.FP32 if args.dtype == "fp32" else oracle.BF16)
+            else:
+                oracle.recon_error(h, c, sc, a)
+            reps += 1
+        dt = (time.perf_counter() - t1) / reps
+        cpu = {"value": es * h.size / dt / 1e9, "unit": f"GB/s {args.dtype} " + ("out" if deq else "in"), "cores": oracle.threads(),
+               "kind": "oracle", "seconds": dt, "weights_per_s": h.size / dt,
+               "sample": f"tensor {k} ({specs[k].name}, {h.size} weights), {reps} repetitions"}
+    print(json.dumps({
+        "metric": "nvfp4_dequantize_throughput" if deq else "nvfp4_recon_error_throughput",
+        "value": es * E / (ms_per_step * 1e-3) / 1e9, "unit": f"GB/s {args.dtype} " + ("out" if deq else "in"), "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
+                   "entry_point": "soar_dequantize" if deq else "soar_recon_error", "algorithm": args.algorithm,
+                   "stored_form": "single-step SOAR output, resident in HBM"},
+        "weights_per_s": E / (ms_per_step * 1e-3), "hbm_frac_of_step": per_w * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        **extra, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu}))
 
 
 def bench_mxfp4(args, torch, B, synth, dev):

@@ -191,48 +191,88 @@ __device__ __forceinline__ void load_block(const void *base, size_t elem_off, fl
     }
 }
 
-// 16-byte pieces of one block of NELEM elements
-template <int DT, int NELEM>
-constexpr int pieces_per_block() { return NELEM * (DT == SOAR_BF16 ? 2 : 4) / 16; }
-
 // The 64 consecutive blocks of a wave lie in one contiguous range when the rows of the tensor are
-// packed (ld == cols).  The wave reads that range in fully coalesced 16-byte pieces (lane l takes
-// pieces l, l + 64, ...: a lane that reads its own 32, 64 or 128 contiguous bytes touches every cache
-// line of the range with every load instruction instead), then each lane picks the pieces of its own
-// block out of a wave-private LDS region of 64 * P pieces.  Inside a block's slots the pieces are
-// rotated by the block's row of 256 bytes, so that neither side has bank conflicts.  Data movement
-// only: w[] ends up exactly as load_block leaves it.  Blocks at or beyond nblk read as zeros.
-// The wave's LDS operations execute in order, so the exchange needs no workgroup barrier.
-template <int DT, int NELEM, bool STREAM>
-__device__ __forceinline__ void load_wave_blocks(const void *base, uint32_t wave_first, uint32_t nblk,
-                                                 u32x4 *s_wave, float w[NELEM])
+// packed (ld == cols): 64 * P pieces of 16 bytes.  A lane that reads or writes its own 32, 64 or 128
+// contiguous bytes touches every cache line of the range with every instruction; the wave moves the
+// range in fully coalesced pieces instead (lane l takes pieces l, l + 64, ...) and each lane finds
+// the P pieces of its own block in a wave-private LDS region of 64 * P pieces.  Inside a block's
+// slots the pieces are rotated by the block's row of 256 bytes, so that neither side of the exchange
+// has bank conflicts.  A wave's LDS operations execute in order: no workgroup barrier is needed.
+// Data movement only.  `have` = pieces of the range that exist (the tensor may end inside it).
+template <int P>
+__device__ __forceinline__ uint32_t exchange_slot(uint32_t block, uint32_t piece)
 {
-    constexpr int P = pieces_per_block<DT, NELEM>();
-    constexpr uint32_t kPerRow = 16 / P;                 // blocks per 256 bytes of LDS
     static_assert(P == 2 || P == 4 || P == 8, "block of 32, 64 or 128 bytes");
+    return block * (uint32_t)P + ((piece + block / (uint32_t)(16 / P)) & (uint32_t)(P - 1));
+}
+
+template <int P, bool STREAM>
+__device__ __forceinline__ void load_wave_pieces(const u32x4 *range, uint32_t have, u32x4 *s_wave, u32x4 v[P])
+{
     const uint32_t lane = threadIdx.x & 63u;
-    const u32x4 *g = static_cast<const u32x4 *>(base) + (size_t)wave_first * P;
-    const uint32_t have = wave_first < nblk ? min(64u, nblk - wave_first) * (uint32_t)P : 0u;
-    u32x4 v[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const uint32_t idx = (uint32_t)p * 64u + lane;
         v[p] = u32x4{0u, 0u, 0u, 0u};
-        if (idx < have) v[p] = load16<STREAM>(g + idx);
+        if (idx < have) v[p] = load16<STREAM>(range + idx);
     }
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const uint32_t idx = (uint32_t)p * 64u + lane;
-        const uint32_t u = idx / (uint32_t)P, piece = idx % (uint32_t)P;
-        s_wave[u * P + ((piece + u / kPerRow) & (uint32_t)(P - 1))] = v[p];
+        s_wave[exchange_slot<P>(idx / (uint32_t)P, idx % (uint32_t)P)] = v[p];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int p = 0; p < P; ++p) v[p] = s_wave[lane * P + (((uint32_t)p + lane / kPerRow) & (uint32_t)(P - 1))];
+    for (int p = 0; p < P; ++p) v[p] = s_wave[exchange_slot<P>(lane, (uint32_t)p)];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();                     // the next exchange writes these slots again
+}
+
+template <int P, bool STREAM>
+__device__ __forceinline__ void store_wave_pieces(u32x4 *range, uint32_t have, u32x4 *s_wave, const u32x4 v[P])
+{
+    const uint32_t lane = threadIdx.x & 63u;
+#pragma unroll
+    for (int p = 0; p < P; ++p) s_wave[exchange_slot<P>(lane, (uint32_t)p)] = v[p];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint32_t idx = (uint32_t)p * 64u + lane;
+        const u32x4 x = s_wave[exchange_slot<P>(idx / (uint32_t)P, idx % (uint32_t)P)];
+        if (idx < have) {
+            if constexpr (STREAM) __builtin_nontemporal_store(x, range + idx);
+            else range[idx] = x;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// 16-byte pieces of one block of NELEM elements
+template <int DT, int NELEM>
+constexpr int pieces_per_block() { return NELEM * (DT == SOAR_BF16 ? 2 : 4) / 16; }
+
+// pieces of the wave's range [wave_first, wave_first + 64) that lie inside a tensor of nblk blocks
+template <int P>
+__device__ __forceinline__ uint32_t wave_pieces(uint32_t wave_first, uint32_t nblk)
+{
+    return wave_first < nblk ? min(64u, nblk - wave_first) * (uint32_t)P : 0u;
+}
+
+// load_block for every lane of a wave at once through the coalescing exchange: w[] ends up exactly
+// as load_block leaves it; blocks at or beyond nblk read as zeros
+template <int DT, int NELEM, bool STREAM>
+__device__ __forceinline__ void load_wave_blocks(const void *base, uint32_t wave_first, uint32_t nblk,
+                                                 u32x4 *s_wave, float w[NELEM])
+{
+    constexpr int P = pieces_per_block<DT, NELEM>();
+    u32x4 v[P];
+    load_wave_pieces<P, STREAM>(static_cast<const u32x4 *>(base) + (size_t)wave_first * P, wave_pieces<P>(wave_first, nblk),
+                                s_wave, v);
     if constexpr (DT == SOAR_BF16) {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
@@ -249,6 +289,36 @@ __device__ __forceinline__ void load_wave_blocks(const void *base, uint32_t wave
             w[4 * p] = f_of(v[p].x); w[4 * p + 1] = f_of(v[p].y); w[4 * p + 2] = f_of(v[p].z); w[4 * p + 3] = f_of(v[p].w);
         }
     }
+}
+
+// NELEM values of a lane's block to the output element type and out through the exchange
+template <int DT, int NELEM>
+__device__ __forceinline__ void store_wave_blocks(void *base, uint32_t wave_first, uint32_t nblk, u32x4 *s_wave,
+                                                  const float v[NELEM])
+{
+    constexpr int P = pieces_per_block<DT, NELEM>();
+    u32x4 x[P];
+    if constexpr (DT == SOAR_BF16) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            uint32_t u[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                f2 in = {v[8 * p + 2 * k], v[8 * p + 2 * k + 1]};
+                bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
+                __builtin_memcpy(&u[k], &o, 4);
+            }
+            x[p] = u32x4{u[0], u[1], u[2], u[3]};
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            x[p] = u32x4{__float_as_uint(v[4 * p]), __float_as_uint(v[4 * p + 1]), __float_as_uint(v[4 * p + 2]),
+                         __float_as_uint(v[4 * p + 3])};
+    }
+    store_wave_pieces<P, true>(static_cast<u32x4 *>(base) + (size_t)wave_first * P, wave_pieces<P>(wave_first, nblk), s_wave, x);
 }
 
 __device__ __forceinline__ size_t block_offset(const Geom &g, uint32_t i)
@@ -725,6 +795,11 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     __shared__ double s_tree[kWG];
     __shared__ double s_stack[16];
     __shared__ uint32_t s_last;
+    // The coalescing exchange pays where the reads bound the kernel: binary32 input (64 bytes per lane)
+    // and the plain conversion.  The bf16 search is as much bound by its arithmetic and gains nothing.
+    constexpr bool kExchange = DT == SOAR_FP32 || METHOD == SOAR_METHOD_RTN;
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ u32x4 s_x[kExchange ? kWG * kP : 1];    // load_wave_blocks: one region per wave
 
     uint32_t lwg;
     const Task t = batch.t[find_task(batch, lwg)];
@@ -750,10 +825,18 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     double sse = 0.0;
     for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
         const uint32_t i = (k * t.n_wg + lwg) * kWG + tid;
-        if (i >= t.nblk) break;
         float w[16], q[16];
         uint32_t nib[2];
-        load_block<DT, kStreamSearch>(t.w, block_offset(t, i), w);
+        if (kExchange && t.contiguous) {
+            // packed rows: the wave reads its 64 blocks coalesced (all of its lanes take part)
+            const uint32_t wave_first = i - (tid & 63u);
+            if (wave_first >= t.nblk) break;
+            load_wave_blocks<DT, 16, kStreamSearch>(t.w, wave_first, t.nblk, s_x + (tid >> 6) * (64 * kP), w);
+            if (i >= t.nblk) break;
+        } else {
+            if (i >= t.nblk) break;
+            load_block<DT, kStreamSearch>(t.w, block_offset(t, i), w);
+        }
         uint32_t out_code;
         float out_err;
         if (allzero) {
@@ -1517,19 +1600,33 @@ template <int DT>
 __global__ __launch_bounds__(kWG) void k_mx_dequant(const uint8_t *codes, const uint8_t *scales, uint32_t nblk,
                                                     uint32_t bpr, int64_t ld, uint32_t contiguous, void *out)
 {
+    constexpr int kP = pieces_per_block<DT, 32>();
+    __shared__ u32x4 s_x[kWG * kP];                    // store_wave_blocks: one region per wave
     const uint32_t i = blockIdx.x * kWG + threadIdx.x;
-    if (i >= nblk) return;
-    const uint32_t e = scales[i];
-    if (e == 255u) return;
-    const float s = e8m0_value((int)e);
-    const uint4 nb = reinterpret_cast<const uint4 *>(codes)[i];
+    const uint32_t wave_first = i - (threadIdx.x & 63u);
+    if (wave_first >= nblk) return;
+    const bool inside = i < nblk;
+    const uint32_t e = inside ? (uint32_t)__builtin_nontemporal_load(scales + i) : 127u;
+    const bool skip = e == 255u;                        // not a scale: the block's output is left alone
     float v[32];
-    fp4x8_values(nb.x, v);
-    fp4x8_values(nb.y, v + 8);
-    fp4x8_values(nb.z, v + 16);
-    fp4x8_values(nb.w, v + 24);
 #pragma unroll
-    for (int j = 0; j < 32; ++j) v[j] = v[j] * s;
+    for (int j = 0; j < 32; ++j) v[j] = 0.0f;
+    if (inside && !skip) {
+        const float s = e8m0_value((int)e);
+        const u32x4 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes) + i);
+        fp4x8_values(nb.x, v);
+        fp4x8_values(nb.y, v + 8);
+        fp4x8_values(nb.z, v + 16);
+        fp4x8_values(nb.w, v + 24);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) v[j] = v[j] * s;
+    }
+    // packed rows: the wave writes its 64 blocks in coalesced pieces, unless one of them is to be skipped
+    if (contiguous && __builtin_amdgcn_ballot_w64(skip) == 0ull) {
+        store_wave_blocks<DT, 32>(out, wave_first, nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
+        return;
+    }
+    if (!inside || skip) return;
     size_t off;
     if (contiguous) {
         off = (size_t)i * 32;
@@ -1562,16 +1659,30 @@ template <int DT>
 __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
                                                  const float *d_global_scale, Task g, void *out)
 {
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ u32x4 s_x[kWG * kP];                    // store_wave_blocks: one region per wave
     const uint32_t i = blockIdx.x * kWG + threadIdx.x;
-    if (i >= g.nblk) return;
-    const float s = *d_global_scale * e4m3_value(scales[i]);
-    const uint2 nb = reinterpret_cast<const uint2 *>(codes)[i];
-    float q[16];
-    fp4x8_values(nb.x, q);
-    fp4x8_values(nb.y, q + 8);
+    const uint32_t wave_first = i - (threadIdx.x & 63u);
+    if (wave_first >= g.nblk) return;
     float v[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) v[j] = q[j] * s;
+    for (int j = 0; j < 16; ++j) v[j] = 0.0f;
+    if (i < g.nblk) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const float s = *d_global_scale * e4m3_value(__builtin_nontemporal_load(scales + i));
+        const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+        float q[16];
+        fp4x8_values(nb.x, q);
+        fp4x8_values(nb.y, q + 8);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = q[j] * s;
+    }
+    if (g.contiguous) {
+        // packed rows: the wave writes its 64 blocks in coalesced pieces (all of its lanes take part)
+        store_wave_blocks<DT, 16>(out, wave_first, g.nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
+        return;
+    }
+    if (i >= g.nblk) return;
     const size_t off = block_offset(g, i);
     if constexpr (DT == SOAR_BF16) {
         typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -1595,27 +1706,44 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uin
 
 __global__ void k_zero_f64(double *p) { *p = 0.0; }
 
-// Eq. 4 for stored codes and scales
+// Eq. 4 for stored codes and scales.  Every workgroup ends with one binary64 atomic addition to the
+// result; additions to one address are served one after the other (thousands of them cost more than
+// the reads of a whole tensor), so the workgroups are few and large: 16 waves each, at most kReconGrid.
+constexpr int kReconWG = 1024;
+constexpr uint32_t kReconGrid = 512;
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_recon(Task g, const uint8_t *codes, const uint8_t *scales,
-                                               const float *d_global_scale, double *d_sse)
+__global__ __launch_bounds__(kReconWG) void k_recon(Task g, const uint8_t *codes, const uint8_t *scales,
+                                                    const float *d_global_scale, double *d_sse)
 {
-    __shared__ double s_wave[4];
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ u32x4 s_x[kReconWG * kP];               // load_wave_blocks: one region per wave
+    __shared__ double s_wave[kReconWG / 64];
     const uint32_t tid = threadIdx.x;
     const float alpha = *d_global_scale;
     double sse = 0.0;
-    for (uint32_t i = blockIdx.x * kWG + tid; i < g.nblk; i += gridDim.x * kWG) {
+    // the workgroups in flight sweep one contiguous window of memory
+    for (uint32_t first = blockIdx.x * kReconWG; first < g.nblk; first += gridDim.x * kReconWG) {
+        const uint32_t i = first + tid;
+        const bool inside = i < g.nblk;
         float w[16], q[16];
-        load_block<DT>(g.w, block_offset(g, i), w);
-        const uint2 nb = reinterpret_cast<const uint2 *>(codes)[i];
-        fp4x8_values(nb.x, q);
-        fp4x8_values(nb.y, q + 8);
-        sse += (double)block_error(w, q, alpha * e4m3_value(scales[i]));
+        if (g.contiguous) load_wave_blocks<DT, 16, true>(g.w, i - (tid & 63u), g.nblk, s_x + (tid >> 6) * (64 * kP), w);
+        else if (inside) load_block<DT, false>(g.w, block_offset(g, i), w);
+        if (inside) {
+            const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+            fp4x8_values(nb.x, q);
+            fp4x8_values(nb.y, q + 8);
+            sse += (double)block_error(w, q, alpha * e4m3_value(__builtin_nontemporal_load(scales + i)));
+        }
     }
     sse = wave_pair_tree(sse);
     if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
     __syncthreads();
-    if (tid == 0) atomicAdd(d_sse, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
+    if (tid < 64) {
+        double v = tid < kReconWG / 64 ? s_wave[tid] : 0.0;
+        v = wave_pair_tree(v);
+        if (tid == 0) atomicAdd(d_sse, v);
+    }
 }
 
 __global__ void k_e2m1_round(const float *x, int64_t n, uint8_t *out)
@@ -2120,15 +2248,15 @@ soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, in
     if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     Task g = make_task(d_w, rows, cols, ld_elems, 0);
-    uint32_t grid = (g.nblk + kWG - 1) / kWG;
-    if (grid > 2048) grid = 2048;
+    uint32_t grid = (g.nblk + kReconWG - 1) / kReconWG;
+    if (grid > kReconGrid) grid = kReconGrid;
     ScopedTimer t(SOAR_KERNEL_RECON, st);
     hipLaunchKernelGGL(k_zero_f64, dim3(1), dim3(1), 0, st, d_sse);
     SOAR_LAUNCH_CHECK();
     if (dtype == SOAR_BF16)
-        hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
+        hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(grid), dim3(kReconWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
     else
-        hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
+        hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(grid), dim3(kReconWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
     SOAR_LAUNCH_CHECK();
     return SOAR_OK;
 }

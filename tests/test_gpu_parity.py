@@ -195,6 +195,22 @@ def test_fp32_input_and_leading_dimension():
         assert float(back[:, 528:].abs().sum().item()) == 0.0       # padding untouched
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 16), (3, 48), (257, 272), (1000, 1040), (5, 8192 * 2 + 16)])
+def test_dequantize_and_recon_error_ragged_waves(rows, cols):
+    """Packed rows go through the coalescing exchange of the load and store paths: tensors that end inside a
+    wave's 64 blocks, both element types, against the oracle's Eq. 3 and Eq. 4."""
+    g = torch.Generator(device="cpu").manual_seed(rows * 131 + cols)
+    f = torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g)) * 0.05
+    for w in (f.to(torch.bfloat16).to(DEV), (f * 1.0009765625).to(DEV)):
+        out, ref = check_against_oracle(w, B.SOAR_METHOD_SOAR, 4, what=f"{rows}x{cols} {w.dtype}")
+        back = B.dequantize(out, torch.bfloat16).cpu().view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(back, oracle.dequantize(ref.codes, ref.scales, ref.global_scale, oracle.BF16))
+        back32 = B.dequantize(out, torch.float32).cpu().numpy()
+        assert np.array_equal(back32, oracle.dequantize(ref.codes, ref.scales, ref.global_scale, oracle.FP32))
+        assert math.isclose(float(B.recon_error(w, out).item()), ref.sse, rel_tol=REL)
+        assert math.isclose(oracle.recon_error(np_weights(w), ref.codes, ref.scales, ref.global_scale), ref.sse, rel_tol=REL)
+
+
 # ----------------------------------------------------------------- degenerate inputs
 def test_extreme_magnitudes_and_subnormal_scales():
     g = torch.Generator(device="cpu").manual_seed(9)

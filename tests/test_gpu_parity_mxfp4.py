@@ -119,6 +119,31 @@ def test_fp32_strided_extreme_magnitudes_zero_and_non_finite():
     assert int(again.status.item()) == 0
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 32), (3, 96), (257, 288), (70, 2080)])
+def test_dequantize_ragged_waves_and_a_byte_that_is_no_scale(rows, cols):
+    """Packed rows are written through the coalescing exchange; a block whose scale byte is 255 is left as
+    it was (the wave that holds it falls back to lane-wise stores)."""
+    g = torch.Generator(device="cpu").manual_seed(rows * 17 + cols)
+    w = (torch.randn(rows, cols, generator=g) * 0.1).to(torch.bfloat16).to(DEV)
+    q = B.mx_quantize(w, B.soar_mx_default_params(dss=False))
+    torch.cuda.synchronize()
+    codes, scales = q.codes.cpu().numpy(), q.scales.cpu().numpy().copy()
+    for dt, odt in ((torch.bfloat16, oracle.BF16), (torch.float32, oracle.FP32)):
+        back = B.mx_dequantize(q, dt).cpu()
+        got = back.view(torch.int16).numpy().view(np.uint16) if dt == torch.bfloat16 else back.numpy()
+        assert np.array_equal(got, oracle.mxfp4_dequantize(codes, scales, odt))
+    flat = scales.reshape(-1)
+    flat[:: max(1, flat.size // 5)] = 255
+    d_scales = torch.from_numpy(scales).to(DEV)
+    for dt, odt, code in ((torch.bfloat16, oracle.BF16, B.SOAR_BF16), (torch.float32, oracle.FP32, B.SOAR_FP32)):
+        out = torch.zeros((rows, cols), dtype=dt, device=DEV)
+        rc = B.soar_mxfp4_dequantize(q.codes.data_ptr(), d_scales.data_ptr(), rows, cols, code, out.data_ptr(), cols, 0)
+        assert rc == 0
+        torch.cuda.synchronize()
+        got = out.cpu().view(torch.int16).numpy().view(np.uint16) if dt == torch.bfloat16 else out.cpu().numpy()
+        assert np.array_equal(got, oracle.mxfp4_dequantize(codes, scales, odt))
+
+
 def test_full_size_tensors_of_the_model_workload_sampled():
     """bench.py --algorithm mxfp4-dss calls the entry point once per tensor of config 4; here: the first
     tensor and one wide MLP tensor at full size, with the default search settings."""
