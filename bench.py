@@ -31,7 +31,7 @@ BYTES_ABSMAX = 2.0
 # (profiles/config4_hbm_traffic_pmc.md): 2.2605 read + 0.5805 written.
 SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2605 + 0.5805
 # the same for the one-pass plain NVFP4 with a supplied maximum (profiles/config4_rtn_amax.md)
-RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0201 + 0.5795
+RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0015 + 0.5766
 # Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
 # method needs 16 products w*r, 16 roundings onto E2M1, 16 decoded values and, per stored-scale
 # candidate, 16 residuals (one fused op each) and 16 fused square-accumulates.
