@@ -1,0 +1,119 @@
+// Kernels on the stored NVFP4 form: k_dequant (Eq. 3), k_recon (Eq. 4), and the element-wise
+// format kernels the tests use.
+#pragma once
+#include "soar_device.hpp"
+
+namespace {
+
+
+// Eq. 3
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
+                                                 const float *d_global_scale, Task g, void *out)
+{
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ u32x4 s_x[kWG * kP];                    // store_wave_blocks: one region per wave
+    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    const uint32_t wave_first = i - (threadIdx.x & 63u);
+    if (wave_first >= g.nblk) return;
+    float v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = 0.0f;
+    if (i < g.nblk) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const float s = *d_global_scale * e4m3_value(__builtin_nontemporal_load(scales + i));
+        const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+        float q[16];
+        fp4x8_values(nb.x, q);
+        fp4x8_values(nb.y, q + 8);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = q[j] * s;
+    }
+    if (g.contiguous) {
+        // packed rows: the wave writes its 64 blocks in coalesced pieces (all of its lanes take part)
+        store_wave_blocks<DT, 16>(out, wave_first, g.nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
+        return;
+    }
+    if (i >= g.nblk) return;
+    const size_t off = block_offset(g, i);
+    if constexpr (DT == SOAR_BF16) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        uint32_t u[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            f2 in = {v[2 * k], v[2 * k + 1]};
+            bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
+            __builtin_memcpy(&u[k], &o, 4);
+        }
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + off);
+        p[0] = make_uint4(u[0], u[1], u[2], u[3]);
+        p[1] = make_uint4(u[4], u[5], u[6], u[7]);
+    } else {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    }
+}
+
+__global__ void k_zero_f64(double *p) { *p = 0.0; }
+
+// Eq. 4 for stored codes and scales.  Every workgroup ends with one binary64 atomic addition to the
+// result; additions to one address are served one after the other (thousands of them cost more than
+// the reads of a whole tensor), so the workgroups are few and large: 16 waves each, at most kReconGrid.
+constexpr int kReconWG = 1024;
+constexpr uint32_t kReconGrid = 512;
+template <int DT>
+__global__ __launch_bounds__(kReconWG) void k_recon(Task g, const uint8_t *codes, const uint8_t *scales,
+                                                    const float *d_global_scale, double *d_sse)
+{
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ u32x4 s_x[kReconWG * kP];               // load_wave_blocks: one region per wave
+    __shared__ double s_wave[kReconWG / 64];
+    const uint32_t tid = threadIdx.x;
+    const float alpha = *d_global_scale;
+    double sse = 0.0;
+    // the workgroups in flight sweep one contiguous window of memory
+    for (uint32_t first = blockIdx.x * kReconWG; first < g.nblk; first += gridDim.x * kReconWG) {
+        const uint32_t i = first + tid;
+        const bool inside = i < g.nblk;
+        float w[16], q[16];
+        if (g.contiguous) load_wave_blocks<DT, 16, true>(g.w, i - (tid & 63u), g.nblk, s_x + (tid >> 6) * (64 * kP), w);
+        else if (inside) load_block<DT, false>(g.w, block_offset(g, i), w);
+        if (inside) {
+            const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+            fp4x8_values(nb.x, q);
+            fp4x8_values(nb.y, q + 8);
+            sse += (double)block_error(w, q, alpha * e4m3_value(__builtin_nontemporal_load(scales + i)));
+        }
+    }
+    sse = wave_pair_tree(sse);
+    if ((tid & 63) == 0) s_wave[tid >> 6] = sse;
+    __syncthreads();
+    if (tid < 64) {
+        double v = tid < kReconWG / 64 ? s_wave[tid] : 0.0;
+        v = wave_pair_tree(v);
+        if (tid == 0) atomicAdd(d_sse, v);
+    }
+}
+
+__global__ void k_e2m1_round(const float *x, int64_t n, uint8_t *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (uint8_t)(__builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, x[i], 0.0f, 1.0f, 0) & 0xFu);
+}
+
+__global__ void k_e4m3_project(const float *x, int64_t n, uint8_t *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = (uint8_t)e4m3_project(x[i]);
+}
+
+__global__ void k_rcp_midrange(const float *x, int64_t n, float *out)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = rcp_midrange(x[i]);
+}
+
+}  // namespace
