@@ -29,7 +29,7 @@ BYTES_ABSMAX = 2.0
 # HBM bytes per weight the search kernel really moves on the full-model workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
 # (profiles/config4_hbm_traffic_pmc.md): 2.2605 read + 0.5805 written.
-SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2605 + 0.5805
+SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2605 + 0.5806
 # the same for the one-pass plain NVFP4 with a supplied maximum (profiles/config4_rtn_amax.md)
 RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0015 + 0.5766
 # Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
