@@ -89,6 +89,8 @@ def parse_args():
                     help="after the timed region: this many separately timed steps, reported as median and min (0 = none)")
     ap.add_argument("--cold", action="store_true",
                     help="with --reps: write a 1 GiB scratch buffer before every repetition (caches hold none of the input)")
+    ap.add_argument("--per-tensor", action="store_true",
+                    help="--algorithm dequantize / recon-error: one call per tensor instead of the batch entry point")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -402,8 +404,9 @@ def main():
 
 
 def bench_stored_form(args, torch, B, synth, dev):
-    """Eq. 3 (soar_dequantize) or Eq. 4 (soar_recon_error) over every tensor of the workload, one call
-    per tensor on the current stream, on the stored form the single-step path produced."""
+    """Eq. 3 (soar_dequantize_batch) or Eq. 4 (soar_recon_error_batch) over every tensor of the workload, on
+    the stored form the single-step path produced; --per-tensor: one soar_dequantize / soar_recon_error call
+    per tensor instead."""
     import numpy as np
     specs = synth.workload_specs(args.workload)
     per_layer = {4: 7, 5: 3}.get(args.workload, 1)
@@ -418,18 +421,29 @@ def bench_stored_form(args, torch, B, synth, dev):
     torch.cuda.synchronize()
     E = sum(s.numel for s in specs)
     st = torch.cuda.current_stream().cuda_stream
+    one_by_one = args.per_tensor
     if deq:
         backs = [torch.empty((s.rows, s.cols), dtype=tdt, device=dev) for s in specs]
+        descs = [B.stored_desc(q, out=o) for q, o in zip(qs, backs)]
 
         def step():
+            if not one_by_one:
+                rc = B.soar_dequantize_batch(descs, st)
+                assert rc == B.SOAR_OK, rc
+                return
             for s, q, o in zip(specs, qs, backs):
                 rc = B.soar_dequantize(q.codes.data_ptr(), q.scales.data_ptr(), q.global_scale.data_ptr(), s.rows, s.cols,
                                        code, o.data_ptr(), s.cols, st)
                 assert rc == B.SOAR_OK, rc
     else:
         sses = torch.zeros(len(specs), dtype=torch.float64, device=dev)
+        descs = [B.stored_desc(q, w=w, sse=sses[k:k + 1]) for k, (q, w) in enumerate(zip(qs, weights))]
 
         def step():
+            if not one_by_one:
+                rc = B.soar_recon_error_batch(descs, st)
+                assert rc == B.SOAR_OK, rc
+                return
             for k, (s, q, w) in enumerate(zip(specs, qs, weights)):
                 rc = B.soar_recon_error(w.data_ptr(), code, s.rows, s.cols, s.cols, q.codes.data_ptr(), q.scales.data_ptr(),
                                         q.global_scale.data_ptr(), sses.data_ptr() + 8 * k, st)
@@ -461,8 +475,9 @@ def bench_stored_form(args, torch, B, synth, dev):
         roofline = {"kernel": kname, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
                     "weights_per_launch": E / (n / n_prof), "avg_launch_us": ms / n * 1e3,
-                    "note": "per-launch HIP-event durations on the launch stream, one launch per tensor"
-                            + ("" if deq else " (with the one-thread launch that clears the sum)")}
+                    "note": "per-launch HIP-event durations on the launch stream, "
+                            + ("one launch per tensor" if one_by_one else "up to 8 tensors per launch")
+                            + ("" if deq else " (with the small launch that clears the sums)")}
     extra = {}
     if not deq:
         got = float(sses.sum().item())
@@ -496,7 +511,8 @@ def bench_stored_form(args, torch, B, synth, dev):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config{args.workload}", "tensors": len(specs), "weights": E,
-                   "entry_point": "soar_dequantize" if deq else "soar_recon_error", "algorithm": args.algorithm,
+                   "entry_point": ("soar_dequantize" if deq else "soar_recon_error") + ("" if one_by_one else "_batch"),
+                   "algorithm": args.algorithm,
                    "stored_form": "single-step SOAR output, resident in HBM"},
         "weights_per_s": E / (ms_per_step * 1e-3), "hbm_frac_of_step": per_w * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         **extra, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu}))

@@ -232,6 +232,38 @@ soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, in
                              const float *d_global_scale, double *d_sse, void *hip_stream);
 
 /*
+ * Eq. 3 and Eq. 4 for the stored tensors of a whole model in a handful of launches:
+ * up to 8 tensors of one element type share a launch, as in soar_quantize_batch.
+ * All pointers are device pointers, owned by the caller; nothing is allocated;
+ * everything is enqueued on hip_stream.
+ *
+ * soar_stored_desc: d_codes (rows*cols/2 bytes, 8-byte aligned), d_scales
+ * (rows*cols/16 bytes), d_global_scale (1 float) as soar_quantize wrote them;
+ * rows, cols, ld_elems and dtype describe the weight matrix -- d_w, read by
+ * soar_recon_error_batch (Eq. 4; d_sse: 1 double, overwritten), or d_out, written
+ * by soar_dequantize_batch (Eq. 3); both 16-byte aligned with ld_elems * element
+ * size a multiple of 16.  The fields the other call uses may be null.
+ * Eq. 3 gives the bytes of the one-tensor call; the Eq. 4 sums agree with it up to
+ * the order of the binary64 additions (workgroup partials are added atomically,
+ * in both forms).  Errors are those of the one-tensor calls, found before anything
+ * is enqueued; n = 0 is a no-op.
+ */
+typedef struct soar_stored_desc {
+    const uint8_t *d_codes;
+    const uint8_t *d_scales;
+    const float   *d_global_scale;
+    int64_t  rows, cols, ld_elems;
+    int32_t  dtype;            /* soar_dtype of d_w / d_out */
+    int32_t  reserved;         /* 0 */
+    const void *d_w;           /* Eq. 4 */
+    void     *d_out;           /* Eq. 3 */
+    double   *d_sse;           /* Eq. 4 */
+} soar_stored_desc;
+
+soar_status soar_dequantize_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream);
+soar_status soar_recon_error_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream);
+
+/*
  * Element-wise projections onto the two small formats, exposed so that the
  * hardware conversion paths can be checked exhaustively (Sec. 3.1 Eq. 2;
  * Appendix D last equation).  d_x: n floats.  d_out: n bytes -- an E2M1 nibble

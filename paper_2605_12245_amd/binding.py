@@ -27,7 +27,8 @@ SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
     "soar_quantize_batch",
-    "soar_dequantize", "soar_recon_error", "soar_e2m1_round_f32", "soar_e4m3_project_f32",
+    "soar_dequantize", "soar_recon_error", "soar_dequantize_batch", "soar_recon_error_batch",
+    "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_rcp_midrange_f32",
     "soar_mx_default_params", "soar_mxfp4_workspace_bytes", "soar_mxfp4_quantize", "soar_mxfp4_dequantize",
     "soar_mxfp4_quantize_batch", "soar_mxfp4_batch_workspace_bytes",
@@ -61,6 +62,15 @@ class soar_mx_params(C.Structure):
         ("struct_size", C.c_uint32), ("dss", C.c_int32), ("n_beta", C.c_int32), ("beta_lo", C.c_float),
         ("beta_hi", C.c_float), ("radius", C.c_int32), ("tiles_per_wg", C.c_int32), ("single_pass", C.c_int32),
         ("streams", C.c_int32),
+    ]
+
+
+class soar_stored_desc(C.Structure):
+    _fields_ = [
+        ("d_codes", C.c_void_p), ("d_scales", C.c_void_p), ("d_global_scale", C.c_void_p),
+        ("rows", C.c_int64), ("cols", C.c_int64), ("ld_elems", C.c_int64),
+        ("dtype", C.c_int32), ("reserved", C.c_int32),
+        ("d_w", C.c_void_p), ("d_out", C.c_void_p), ("d_sse", C.c_void_p),
     ]
 
 
@@ -111,6 +121,10 @@ def lib():
     L.soar_dequantize.restype = i32
     L.soar_recon_error.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp, vp, vp]
     L.soar_recon_error.restype = i32
+    L.soar_dequantize_batch.argtypes = [i32, C.POINTER(soar_stored_desc), vp]
+    L.soar_dequantize_batch.restype = i32
+    L.soar_recon_error_batch.argtypes = [i32, C.POINTER(soar_stored_desc), vp]
+    L.soar_recon_error_batch.restype = i32
     L.soar_e2m1_round_f32.argtypes = [vp, i64, vp, vp]
     L.soar_e2m1_round_f32.restype = i32
     L.soar_e4m3_project_f32.argtypes = [vp, i64, vp, vp]
@@ -272,6 +286,21 @@ def soar_mxfp4_quantize_batch(descs: Sequence[soar_mx_tensor_desc], params, d_wo
 def soar_mxfp4_batch_workspace_bytes(descs: Sequence[soar_mx_tensor_desc], params) -> int:
     arr = (soar_mx_tensor_desc * len(descs))(*descs)
     return int(lib().soar_mxfp4_batch_workspace_bytes(len(descs), arr, C.byref(params)))
+
+
+def _stored_array(descs):
+    arr = (soar_stored_desc * max(1, len(descs)))()
+    for k, d in enumerate(descs):
+        arr[k] = d
+    return arr
+
+
+def soar_dequantize_batch(descs: Sequence["soar_stored_desc"], hip_stream) -> int:
+    return int(lib().soar_dequantize_batch(len(descs), _stored_array(descs), hip_stream))
+
+
+def soar_recon_error_batch(descs: Sequence["soar_stored_desc"], hip_stream) -> int:
+    return int(lib().soar_recon_error_batch(len(descs), _stored_array(descs), hip_stream))
 
 
 def soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream) -> int:
@@ -465,6 +494,42 @@ def recon_error(w: torch.Tensor, q: Quantized) -> torch.Tensor:
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_recon_error")
     return sse
+
+
+def stored_desc(q: Quantized, w: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                sse: Optional[torch.Tensor] = None) -> "soar_stored_desc":
+    """Descriptor of one stored tensor: `w` and `sse` for Eq. 4, `out` for Eq. 3 (the tensors must stay alive
+    until the call that uses the descriptor has been enqueued)."""
+    m = w if w is not None else out
+    rows, cols, ld = _check_matrix(m)
+    d = soar_stored_desc()
+    d.d_codes, d.d_scales, d.d_global_scale = q.codes.data_ptr(), q.scales.data_ptr(), q.global_scale.data_ptr()
+    d.rows, d.cols, d.ld_elems, d.dtype = rows, cols, ld, _dtype_code(m)
+    d.d_w = w.data_ptr() if w is not None else None
+    d.d_out = out.data_ptr() if out is not None else None
+    d.d_sse = sse.data_ptr() if sse is not None else None
+    return d
+
+
+def dequantize_batch(qs: Sequence[Quantized], out_dtype=torch.bfloat16) -> list:
+    """Eq. 3 for a list of stored tensors in a handful of launches."""
+    outs = [torch.empty((q.scales.shape[0], q.scales.shape[1] * 16), dtype=out_dtype, device=q.codes.device) for q in qs]
+    rc = soar_dequantize_batch([stored_desc(q, out=o) for q, o in zip(qs, outs)], _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_dequantize_batch")
+    return outs
+
+
+def recon_error_batch(weights: Sequence[torch.Tensor], qs: Sequence[Quantized]) -> torch.Tensor:
+    """Eq. 4 for a list of tensors in a handful of launches: one binary64 sum per tensor."""
+    if not weights:
+        return torch.empty(0, dtype=torch.float64)
+    sses = torch.empty(len(weights), dtype=torch.float64, device=weights[0].device)
+    rc = soar_recon_error_batch([stored_desc(q, w=w, sse=sses[k:k + 1]) for k, (w, q) in enumerate(zip(weights, qs))],
+                                _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_recon_error_batch")
+    return sses
 
 
 # ------------------------------------------------------------------ MXFP4

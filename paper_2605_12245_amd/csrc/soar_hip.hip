@@ -412,6 +412,82 @@ soar_status check_mx_shape(int64_t rows, int64_t cols, int64_t ld)
     return SOAR_OK;
 }
 
+// ---- Eq. 3 / Eq. 4 on stored tensors: up to kGroupMax tensors of one element type and at most
+// kStoredByteCap bytes of weights per launch
+soar_status validate_stored(const soar_stored_desc &d, bool recon)
+{
+    if (!d.d_codes || !d.d_scales || !d.d_global_scale) return SOAR_ERR_NULL;
+    if (recon ? (!d.d_w || !d.d_sse) : !d.d_out) return SOAR_ERR_NULL;
+    if (d.dtype != SOAR_BF16 && d.dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+    soar_status s = check_shape(d.rows, d.cols, d.ld_elems);
+    if (s != SOAR_OK) return s;
+    s = check_matrix_ptr(recon ? d.d_w : d.d_out, d.dtype, d.ld_elems);
+    if (s != SOAR_OK) return s;
+    if (reinterpret_cast<uintptr_t>(d.d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
+    return SOAR_OK;
+}
+
+// no pass follows that would find the group in the last-level cache: the cap only bounds the grid
+constexpr int64_t kStoredByteCap = (int64_t)1 << 31;
+int32_t stored_group_end(int32_t n, const soar_stored_desc *descs, int32_t i)
+{
+    int64_t bytes = 0;
+    int32_t j = i;
+    while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype) {
+        const int64_t b = descs[j].rows * descs[j].cols * (descs[j].dtype == SOAR_BF16 ? 2 : 4);
+        if (j > i && bytes + b > kStoredByteCap) break;
+        bytes += b;
+        ++j;
+    }
+    return j;
+}
+
+soar_status run_stored_batch(int32_t n, const soar_stored_desc *descs, bool recon, hipStream_t st)
+{
+    if (n < 0) return SOAR_ERR_SHAPE;
+    if (n > 0 && !descs) return SOAR_ERR_NULL;
+    for (int32_t k = 0; k < n; ++k) {
+        soar_status s = validate_stored(descs[k], recon);
+        if (s != SOAR_OK) return s;
+    }
+    for (int32_t i = 0; i < n;) {
+        const int32_t j = stored_group_end(n, descs, i);
+        StoredBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.n = (uint32_t)(j - i);
+        uint32_t wg = 0;
+        for (int32_t k = i; k < j; ++k) {
+            const soar_stored_desc &d = descs[k];
+            StoredTask &t = b.t[k - i];
+            t.codes = d.d_codes; t.scales = d.d_scales; t.gscale = d.d_global_scale;
+            t.w = d.d_w; t.out = d.d_out; t.sse = d.d_sse;
+            t.ld = d.ld_elems;
+            t.bpr = (uint32_t)(d.cols / 16);
+            t.nblk = (uint32_t)(d.rows * (d.cols / 16));
+            t.contiguous = d.ld_elems == d.cols ? 1u : 0u;
+            const uint32_t per_wg = recon ? (uint32_t)kReconWG : (uint32_t)kWG;
+            t.n_wg = (t.nblk + per_wg - 1) / per_wg;
+            if (recon && t.n_wg > kReconGrid) t.n_wg = kReconGrid;
+            t.wg_begin = wg;
+            wg += t.n_wg;
+        }
+        const bool bf16 = descs[i].dtype == SOAR_BF16;
+        ScopedTimer tm(recon ? SOAR_KERNEL_RECON : SOAR_KERNEL_DEQUANT, st);
+        if (recon) {
+            hipLaunchKernelGGL(k_zero_sums, dim3(1), dim3(64), 0, st, b);
+            SOAR_LAUNCH_CHECK();
+            if (bf16) hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(wg), dim3(kReconWG), 0, st, b);
+            else hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(wg), dim3(kReconWG), 0, st, b);
+        } else {
+            if (bf16) hipLaunchKernelGGL(k_dequant<SOAR_BF16>, dim3(wg), dim3(kWG), 0, st, b);
+            else hipLaunchKernelGGL(k_dequant<SOAR_FP32>, dim3(wg), dim3(kWG), 0, st, b);
+        }
+        SOAR_LAUNCH_CHECK();
+        i = j;
+    }
+    return SOAR_OK;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C-ABI
@@ -491,53 +567,41 @@ soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const 
     return run_batch(n, descs, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+soar_status soar_dequantize_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream)
+{
+    return run_stored_batch(n, descs, false, static_cast<hipStream_t>(hip_stream));
+}
+
+soar_status soar_recon_error_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream)
+{
+    return run_stored_batch(n, descs, true, static_cast<hipStream_t>(hip_stream));
+}
+
 soar_status soar_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, const float *d_global_scale,
                             int64_t rows, int64_t cols, soar_dtype out_dtype, void *d_out, int64_t ld_elems,
                             void *hip_stream)
 {
-    if (!d_codes || !d_scales || !d_global_scale || !d_out) return SOAR_ERR_NULL;
-    if (out_dtype != SOAR_BF16 && out_dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
-    soar_status s = check_shape(rows, cols, ld_elems);
-    if (s != SOAR_OK) return s;
-    s = check_matrix_ptr(d_out, out_dtype, ld_elems);
-    if (s != SOAR_OK) return s;
-    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    Task g = make_task(d_out, rows, cols, ld_elems, 0);
-    const uint32_t grid = (g.nblk + kWG - 1) / kWG;
-    ScopedTimer t(SOAR_KERNEL_DEQUANT, st);
-    if (out_dtype == SOAR_BF16)
-        hipLaunchKernelGGL(k_dequant<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, d_global_scale, g, d_out);
-    else
-        hipLaunchKernelGGL(k_dequant<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, d_global_scale, g, d_out);
-    SOAR_LAUNCH_CHECK();
-    return SOAR_OK;
+    soar_stored_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.d_codes = d_codes; d.d_scales = d_scales; d.d_global_scale = d_global_scale;
+    d.rows = rows; d.cols = cols; d.ld_elems = ld_elems;
+    d.dtype = out_dtype;
+    d.d_out = d_out;
+    return run_stored_batch(1, &d, false, static_cast<hipStream_t>(hip_stream));
 }
 
 soar_status soar_recon_error(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
                              const uint8_t *d_codes, const uint8_t *d_scales, const float *d_global_scale,
                              double *d_sse, void *hip_stream)
 {
-    if (!d_w || !d_codes || !d_scales || !d_global_scale || !d_sse) return SOAR_ERR_NULL;
-    if (dtype != SOAR_BF16 && dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
-    soar_status s = check_shape(rows, cols, ld_elems);
-    if (s != SOAR_OK) return s;
-    s = check_matrix_ptr(d_w, dtype, ld_elems);
-    if (s != SOAR_OK) return s;
-    if (reinterpret_cast<uintptr_t>(d_codes) % 8 != 0) return SOAR_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    Task g = make_task(d_w, rows, cols, ld_elems, 0);
-    uint32_t grid = (g.nblk + kReconWG - 1) / kReconWG;
-    if (grid > kReconGrid) grid = kReconGrid;
-    ScopedTimer t(SOAR_KERNEL_RECON, st);
-    hipLaunchKernelGGL(k_zero_f64, dim3(1), dim3(1), 0, st, d_sse);
-    SOAR_LAUNCH_CHECK();
-    if (dtype == SOAR_BF16)
-        hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(grid), dim3(kReconWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
-    else
-        hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(grid), dim3(kReconWG), 0, st, g, d_codes, d_scales, d_global_scale, d_sse);
-    SOAR_LAUNCH_CHECK();
-    return SOAR_OK;
+    soar_stored_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.d_codes = d_codes; d.d_scales = d_scales; d.d_global_scale = d_global_scale;
+    d.rows = rows; d.cols = cols; d.ld_elems = ld_elems;
+    d.dtype = dtype;
+    d.d_w = d_w;
+    d.d_sse = d_sse;
+    return run_stored_batch(1, &d, true, static_cast<hipStream_t>(hip_stream));
 }
 
 soar_status soar_e2m1_round_f32(const float *d_x, int64_t n, uint8_t *d_out, void *hip_stream)

@@ -6,14 +6,43 @@
 namespace {
 
 
+// One stored tensor of a launch: up to kGroupMax tensors share a launch, each with its own range of
+// workgroups, so that small tensors do not pay a launch each.
+struct StoredTask {
+    const uint8_t *codes, *scales;
+    const float *gscale;
+    const void  *w;          // Eq. 4: the weights
+    void        *out;        // Eq. 3: the reconstruction
+    double      *sse;        // Eq. 4: the sum
+    int64_t  ld;
+    uint32_t bpr, nblk, contiguous;
+    uint32_t wg_begin, n_wg;
+};
+
+struct StoredBatch {
+    StoredTask t[kGroupMax];
+    uint32_t n;
+};
+
+__device__ __forceinline__ uint32_t find_task(const StoredBatch &b, uint32_t &lwg)
+{
+    const uint32_t id = blockIdx.x;
+    uint32_t k = 0;
+    for (uint32_t j = 1; j < b.n; ++j)
+        if (id >= b.t[j].wg_begin) k = j;
+    lwg = id - b.t[k].wg_begin;
+    return k;
+}
+
 // Eq. 3
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uint8_t *scales,
-                                                 const float *d_global_scale, Task g, void *out)
+__global__ __launch_bounds__(kWG) void k_dequant(const StoredBatch batch)
 {
     constexpr int kP = pieces_per_block<DT, 16>();
     __shared__ u32x4 s_x[kWG * kP];                    // store_wave_blocks: one region per wave
-    const uint32_t i = blockIdx.x * kWG + threadIdx.x;
+    uint32_t lwg;
+    const StoredTask g = batch.t[find_task(batch, lwg)];
+    const uint32_t i = lwg * kWG + threadIdx.x;
     const uint32_t wave_first = i - (threadIdx.x & 63u);
     if (wave_first >= g.nblk) return;
     float v[16];
@@ -21,8 +50,8 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uin
     for (int j = 0; j < 16; ++j) v[j] = 0.0f;
     if (i < g.nblk) {
         typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-        const float s = *d_global_scale * e4m3_value(__builtin_nontemporal_load(scales + i));
-        const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+        const float s = *g.gscale * e4m3_value(__builtin_nontemporal_load(g.scales + i));
+        const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(g.codes) + i);
         float q[16];
         fp4x8_values(nb.x, q);
         fp4x8_values(nb.y, q + 8);
@@ -31,11 +60,11 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uin
     }
     if (g.contiguous) {
         // packed rows: the wave writes its 64 blocks in coalesced pieces (all of its lanes take part)
-        store_wave_blocks<DT, 16>(out, wave_first, g.nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
+        store_wave_blocks<DT, 16>(g.out, wave_first, g.nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
         return;
     }
     if (i >= g.nblk) return;
-    const size_t off = block_offset(g, i);
+    const size_t off = block_offset(g.contiguous != 0u, g.bpr, g.ld, i);
     if constexpr (DT == SOAR_BF16) {
         typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
         typedef float f2 __attribute__((ext_vector_type(2)));
@@ -46,46 +75,52 @@ __global__ __launch_bounds__(kWG) void k_dequant(const uint8_t *codes, const uin
             bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
             __builtin_memcpy(&u[k], &o, 4);
         }
-        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + off);
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(g.out) + off);
         p[0] = make_uint4(u[0], u[1], u[2], u[3]);
         p[1] = make_uint4(u[4], u[5], u[6], u[7]);
     } else {
-        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(out) + off);
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(g.out) + off);
 #pragma unroll
         for (int k = 0; k < 4; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
     }
 }
 
-__global__ void k_zero_f64(double *p) { *p = 0.0; }
+// clears the sums of a launch of k_recon (a kernel, not a memset: the call may be captured into a graph)
+__global__ void k_zero_sums(const StoredBatch batch)
+{
+    if (threadIdx.x < batch.n) *batch.t[threadIdx.x].sse = 0.0;
+}
 
-// Eq. 4 for stored codes and scales.  Every workgroup ends with one binary64 atomic addition to the
-// result; additions to one address are served one after the other (thousands of them cost more than
-// the reads of a whole tensor), so the workgroups are few and large: 16 waves each, at most kReconGrid.
+// Eq. 4 for stored codes and scales.  Every workgroup ends with one binary64 atomic addition to its
+// tensor's result; additions to one address are served one after the other (thousands of them cost
+// more than the reads of a whole tensor), so the workgroups are few and large: 16 waves each, at most
+// kReconGrid per tensor.
 constexpr int kReconWG = 1024;
 constexpr uint32_t kReconGrid = 512;
 template <int DT>
-__global__ __launch_bounds__(kReconWG) void k_recon(Task g, const uint8_t *codes, const uint8_t *scales,
-                                                    const float *d_global_scale, double *d_sse)
+__global__ __launch_bounds__(kReconWG) void k_recon(const StoredBatch batch)
 {
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     constexpr int kP = pieces_per_block<DT, 16>();
     __shared__ u32x4 s_x[kReconWG * kP];               // load_wave_blocks: one region per wave
     __shared__ double s_wave[kReconWG / 64];
+    uint32_t lwg;
+    const StoredTask g = batch.t[find_task(batch, lwg)];
     const uint32_t tid = threadIdx.x;
-    const float alpha = *d_global_scale;
+    const float alpha = *g.gscale;
     double sse = 0.0;
-    // the workgroups in flight sweep one contiguous window of memory
-    for (uint32_t first = blockIdx.x * kReconWG; first < g.nblk; first += gridDim.x * kReconWG) {
+    // the workgroups of a tensor sweep one contiguous window of memory
+    for (uint32_t first = lwg * kReconWG; first < g.nblk; first += g.n_wg * kReconWG) {
         const uint32_t i = first + tid;
         const bool inside = i < g.nblk;
         float w[16], q[16];
         if (g.contiguous) load_wave_blocks<DT, 16, true>(g.w, i - (tid & 63u), g.nblk, s_x + (tid >> 6) * (64 * kP), w);
-        else if (inside) load_block<DT, false>(g.w, block_offset(g, i), w);
+        else if (inside) load_block<DT, false>(g.w, block_offset(false, g.bpr, g.ld, i), w);
         if (inside) {
-            const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(codes) + i);
+            const u32x2 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(g.codes) + i);
             fp4x8_values(nb.x, q);
             fp4x8_values(nb.y, q + 8);
-            sse += (double)block_error(w, q, alpha * e4m3_value(__builtin_nontemporal_load(scales + i)));
+            sse += (double)block_error(w, q, alpha * e4m3_value(__builtin_nontemporal_load(g.scales + i)));
         }
     }
     sse = wave_pair_tree(sse);
@@ -94,7 +129,7 @@ __global__ __launch_bounds__(kReconWG) void k_recon(Task g, const uint8_t *codes
     if (tid < 64) {
         double v = tid < kReconWG / 64 ? s_wave[tid] : 0.0;
         v = wave_pair_tree(v);
-        if (tid == 0) atomicAdd(d_sse, v);
+        if (tid == 0) atomicAdd(g.sse, v);
     }
 }
 

@@ -105,6 +105,27 @@ def test_host_side_argument_validation():
     assert B.soar_quantize_batch([], p, 0x10000, 1 << 20, 0) == 0
 
 
+def test_stored_form_batch_host_side_argument_validation():
+    def desc(**kw):
+        d = B.soar_stored_desc()
+        d.d_codes, d.d_scales, d.d_global_scale = 0x8, 0x10, 0x20
+        d.rows, d.cols, d.ld_elems, d.dtype = 4, 64, 64, 0
+        d.d_w, d.d_out, d.d_sse = 0x1000, 0x2000, 0x30
+        for k, v in kw.items():
+            setattr(d, k, v)
+        return d
+    for call, own in ((B.soar_dequantize_batch, "d_out"), (B.soar_recon_error_batch, "d_w")):
+        assert call([], 0) == 0
+        assert call([desc(d_codes=0)], 0) == 1 and call([desc(d_global_scale=0)], 0) == 1
+        assert call([desc(**{own: 0})], 0) == 1
+        assert call([desc(), desc(dtype=2)], 0) == 3
+        assert call([desc(cols=60)], 0) == 2 and call([desc(ld_elems=48)], 0) == 2 and call([desc(rows=0)], 0) == 2
+        assert call([desc(**{own: 0x1008})], 0) == 7 and call([desc(ld_elems=68)], 0) == 7
+        assert call([desc(d_codes=0x2004)], 0) == 7
+    assert B.soar_recon_error_batch([desc(d_sse=0)], 0) == 1
+    assert int(B.lib().soar_dequantize_batch(-1, None, None)) == 2 and int(B.lib().soar_recon_error_batch(2, None, None)) == 1
+
+
 def test_product_path_has_no_cpu_route():
     torch = pytest.importorskip("torch")
     w = torch.zeros(16, 16, dtype=torch.bfloat16)

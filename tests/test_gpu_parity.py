@@ -211,6 +211,45 @@ def test_dequantize_and_recon_error_ragged_waves(rows, cols):
         assert math.isclose(oracle.recon_error(np_weights(w), ref.codes, ref.scales, ref.global_scale), ref.sse, rel_tol=REL)
 
 
+def test_stored_form_batch_equals_separate_calls_and_the_oracle():
+    """soar_dequantize_batch / soar_recon_error_batch: 21 tensors of two element types (several launches
+    of one type, then the other), ragged, strided and tiny ones among them."""
+    g = torch.Generator(device="cpu").manual_seed(404)
+    ws = [synth.make_weight(s, DEV) for s in synth.workload_specs(4, 8)[:14]]
+    ws.append((torch.randn(33, 48, generator=g) * 0.3).to(torch.bfloat16).to(DEV))
+    ws.append((torch.randn(1, 16, generator=g)).to(torch.bfloat16).to(DEV))
+    parent = (torch.randn(70, 400, generator=g) * 0.1).to(torch.bfloat16).to(DEV)
+    ws.append(parent[:, 16:16 + 336])                                   # ld > cols
+    ws += [(torch.randn(50, 160, generator=g) * 2.0 ** e).to(DEV) for e in (-20, 0, 30)]
+    pf = (torch.randn(40, 96, generator=g)).to(DEV)
+    ws.append(pf[:, 8:8 + 64])
+    qs = [B.quantize(w, B.SOAR_METHOD_SOAR, 4) for w in ws]
+    torch.cuda.synchronize()
+    # Eq. 4: batch, separate calls, the sum the quantizer reported, the oracle
+    sses = B.recon_error_batch(ws, qs)
+    torch.cuda.synchronize()
+    for k, (w, q) in enumerate(zip(ws, qs)):
+        one = float(B.recon_error(w, q).item())
+        assert math.isclose(float(sses[k].item()), one, rel_tol=1e-12), k
+        assert math.isclose(one, float(q.sse.item()), rel_tol=REL), k
+        host = np_weights(w.contiguous())
+        ref = oracle.recon_error(host, q.codes.cpu().numpy(), q.scales.cpu().numpy(), np.float32(q.global_scale.item()))
+        assert math.isclose(float(sses[k].item()), ref, rel_tol=REL), k
+    # Eq. 3: batch into packed outputs of both types, and into a strided output
+    for dt, odt in ((torch.bfloat16, oracle.BF16), (torch.float32, oracle.FP32)):
+        backs = B.dequantize_batch(qs, dt)
+        torch.cuda.synchronize()
+        for k, (q, b) in enumerate(zip(qs, backs)):
+            assert torch.equal(b, B.dequantize(q, dt)), (dt, k)
+            want = oracle.dequantize(q.codes.cpu().numpy(), q.scales.cpu().numpy(), np.float32(q.global_scale.item()), odt)
+            assert np.array_equal(np_weights(b.cpu()), want), (dt, k)
+    wide = torch.full((33, 48 + 32), 7.0, dtype=torch.bfloat16, device=DEV)
+    rc = B.soar_dequantize_batch([B.stored_desc(qs[14], out=wide[:, :48]), B.stored_desc(qs[15], out=torch.empty(1, 16, dtype=torch.bfloat16, device=DEV))], 0)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(wide[:, :48], B.dequantize(qs[14], torch.bfloat16)) and bool((wide[:, 48:] == 7.0).all())
+
+
 # ----------------------------------------------------------------- degenerate inputs
 def test_extreme_magnitudes_and_subnormal_scales():
     g = torch.Generator(device="cpu").manual_seed(9)
