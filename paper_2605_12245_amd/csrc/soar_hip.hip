@@ -164,12 +164,15 @@ soar_status validate_tensor(const soar_tensor_desc &d, const soar_params *params
 // how many tensors starting at `first` go into one launch
 int64_t weight_bytes(const soar_tensor_desc &d) { return d.rows * d.cols * (d.dtype == SOAR_BF16 ? 2 : 4); }
 
+constexpr int64_t kOnePassByteCap = (int64_t)1 << 29;    // larger launches gain nothing more (measured: 2^29 .. 2^31)
 int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
 {
     int64_t bytes = weight_bytes(descs[first]);
     int32_t j = first + 1;
+    // with the maximum supplied there is one pass only: nothing to keep in the last-level cache
+    const int64_t cap = descs[first].d_amax_in ? kOnePassByteCap : kGroupByteCap;
     while (j < n && j - first < kGroupMax && descs[j].dtype == descs[first].dtype &&
-           bytes + weight_bytes(descs[j]) <= kGroupByteCap) {
+           bytes + weight_bytes(descs[j]) <= cap) {
         bytes += weight_bytes(descs[j]);
         ++j;
     }
@@ -649,8 +652,14 @@ size_t soar_mxfp4_workspace_bytes(int64_t rows, int64_t cols, const soar_mx_para
 
 static int32_t mx_group_end(int32_t n, const soar_mx_tensor_desc *descs, int32_t i)
 {
+    auto bytes_of = [](const soar_mx_tensor_desc &d) { return d.rows * d.cols * (d.dtype == SOAR_BF16 ? 2 : 4); };
+    int64_t bytes = bytes_of(descs[i]);
     int32_t j = i + 1;
-    while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype) ++j;
+    while (j < n && j - i < kGroupMax && descs[j].dtype == descs[i].dtype &&
+           bytes + bytes_of(descs[j]) <= kOnePassByteCap) {
+        bytes += bytes_of(descs[j]);
+        ++j;
+    }
     return j;
 }
 
