@@ -374,7 +374,7 @@ soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, voi
 typedef enum {
     SOAR_KERNEL_INIT = 0, SOAR_KERNEL_ABSMAX = 1, SOAR_KERNEL_STATS = 2, SOAR_KERNEL_SEARCH = 3,
     SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_ITER_INIT = 6, SOAR_KERNEL_ITER = 7,
-    SOAR_KERNEL_MX = 8, SOAR_KERNEL_COUNT = 9
+    SOAR_KERNEL_MX = 8, SOAR_KERNEL_SMALL = 9, SOAR_KERNEL_COUNT = 10
 } soar_kernel_id;
 void        soar_kernel_timing_enable(int enable);
 soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches);

@@ -22,7 +22,7 @@ SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX = 1, 2, 4
 SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 (SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
  SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER, SOAR_KERNEL_MX,
- SOAR_KERNEL_COUNT) = range(10)
+ SOAR_KERNEL_SMALL, SOAR_KERNEL_COUNT) = range(11)
 
 EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",

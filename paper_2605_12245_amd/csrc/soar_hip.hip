@@ -304,6 +304,30 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
     if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
 
+    // one small tensor, default launch shape: the whole path in one workgroup, one launch, no workspace use
+    if (n == 1 && !iterated && !descs[0].d_amax_in && params->tiles_per_wg == 0 &&
+        descs[0].rows * (descs[0].cols / 16) <= (int64_t)kSmallBlocks) {
+        const soar_tensor_desc &d = descs[0];
+        Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, 0);
+        t.codes = d.d_codes;
+        t.scales = d.d_scales;
+        t.gscale = d.d_global_scale;
+        t.sse = d.d_sse;
+        t.status = d.d_status;
+        const int radius = params->dss_radius, full = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        const bool rtn = params->method == SOAR_METHOD_RTN;
+        ScopedTimer tm(SOAR_KERNEL_SMALL, st);
+        if (d.dtype == SOAR_BF16) {
+            if (rtn) hipLaunchKernelGGL((k_small<SOAR_BF16, SOAR_METHOD_RTN>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+            else hipLaunchKernelGGL((k_small<SOAR_BF16, SOAR_METHOD_SOAR>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+        } else {
+            if (rtn) hipLaunchKernelGGL((k_small<SOAR_FP32, SOAR_METHOD_RTN>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+            else hipLaunchKernelGGL((k_small<SOAR_FP32, SOAR_METHOD_SOAR>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+        }
+        SOAR_LAUNCH_CHECK();
+        return SOAR_OK;
+    }
+
     int32_t n_groups = 0;
     const size_t lane_bytes = lane_workspace_bytes(max_group_per_block_bytes(n, descs, &n_groups));
     const int lanes = (n_groups > 1 && params->streams != 1) ? kLanes : 1;

@@ -383,4 +383,171 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     reset_counters(counters, &t.ctrl->top[2]);
 }
 
+// The whole single-step path for one small tensor in one workgroup: a tensor of at most
+// kSmallBlocks blocks is latency-bound on the four dependent launches of the path above; here the
+// 1024 lanes keep their (up to four) blocks in registers, and the two tensor-wide results cross
+// the workgroup through LDS and a barrier.  Same arithmetic, same trees: lane `tid` owns the
+// blocks tid, tid + 1024, ...; a wave's DPP tree sums 64 consecutive blocks, and the 4 x 16 wave
+// sums, laid out in block order over the lanes of wave 0, go through the same DPP tree again --
+// together the adjacent-pair tree over the flat block index, zero-padded.  No workspace is used.
+constexpr int kSmallWG = 1024;
+constexpr int kSmallPer = 4;                               // blocks per lane, at most
+constexpr uint32_t kSmallBlocks = kSmallWG * kSmallPer;
+template <int DT, int METHOD>
+__global__ __launch_bounds__(kSmallWG) void k_small(const Task t, const int radius, const int full_search)
+{
+    constexpr int kWaves = kSmallWG / 64;
+    constexpr int kP = pieces_per_block<DT, 16>();
+    __shared__ uint32_t s_max[kWaves];
+    __shared__ double s_part[3][kSmallPer * kWaves];
+    __shared__ float s_alpha1;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+
+    // ---- the blocks of this lane, as loaded; Eq. 1 maximum
+    u32x4 raw[kSmallPer][kP];
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < kSmallPer; ++k) {
+        const uint32_t i = (uint32_t)k * kSmallWG + tid;
+#pragma unroll
+        for (int p = 0; p < kP; ++p) raw[k][p] = u32x4{0u, 0u, 0u, 0u};
+        if (i < t.nblk) {
+            const char *src = static_cast<const char *>(t.w) + block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
+#pragma unroll
+            for (int p = 0; p < kP; ++p) {
+                raw[k][p] = load16<false>(src + 16 * p);
+                m = absmax_accumulate<DT>(m, make_uint4(raw[k][p].x, raw[k][p].y, raw[k][p].z, raw[k][p].w));
+            }
+        }
+    }
+    if constexpr (DT == SOAR_BF16) m = max(m & 0xFFFFu, m >> 16) << 16;
+    m = wave_max_u32(m);
+    if (lane == 0) s_max[wave] = m;
+    __syncthreads();
+    uint32_t amax_bits = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < kWaves; ++w2) amax_bits = max(amax_bits, s_max[w2]);
+    const bool allzero = amax_bits == 0u;
+    const bool degenerate = allzero || amax_bits >= 0x7F800000u;
+    const float alpha0 = f_of(amax_bits) / 2688.0f;
+    const float alpha0_m = alpha0 * 6.0f;
+
+    auto widen = [&](int k, float w[16]) {
+        if constexpr (DT == SOAR_BF16) {
+#pragma unroll
+            for (int p = 0; p < kP; ++p) {
+                const uint32_t u[4] = {raw[k][p].x, raw[k][p].y, raw[k][p].z, raw[k][p].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    w[8 * p + 2 * e] = f_of(u[e] << 16);
+                    w[8 * p + 2 * e + 1] = f_of(u[e] & 0xFFFF0000u);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < kP; ++p) {
+                w[4 * p] = f_of(raw[k][p].x); w[4 * p + 1] = f_of(raw[k][p].y);
+                w[4 * p + 2] = f_of(raw[k][p].z); w[4 * p + 3] = f_of(raw[k][p].w);
+            }
+        }
+    };
+    // sum of one binary64 term per block over the tensor: every lane of the workgroup calls it
+    auto tensor_sum = [&](int which, const double term[kSmallPer]) -> double {
+#pragma unroll
+        for (int k = 0; k < kSmallPer; ++k) {
+            const double v = wave_pair_tree(term[k]);
+            if (lane == 0) s_part[which][k * kWaves + wave] = v;
+        }
+        __syncthreads();
+        return wave_pair_tree(s_part[which][lane]);        // 4 x 16 wave sums in block order
+    };
+
+    // ---- Eq. 1-2 state and Eq. 5
+    float alpha1 = alpha0;
+    float rho[kSmallPer];
+#pragma unroll
+    for (int k = 0; k < kSmallPer; ++k) rho[k] = 0.0f;
+    if constexpr (METHOD == SOAR_METHOD_SOAR) {
+        double tN[kSmallPer], tM[kSmallPer];
+#pragma unroll
+        for (int k = 0; k < kSmallPer; ++k) {
+            tN[k] = tM[k] = 0.0;
+            const uint32_t i = (uint32_t)k * kSmallWG + tid;
+            if (i < t.nblk && !degenerate) {
+                float w[16], q[16];
+                uint32_t nib[2], c0;
+                float delta0, a, b;
+                widen(k, w);
+                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                block_sums(w, q, a, b);
+                tN[k] = (double)a * (double)delta0;
+                tM[k] = ((double)b * (double)delta0) * (double)delta0;
+                rho[k] = (b == 0.0f) ? -delta0 : a / b;      // first half of Eq. 6
+            }
+        }
+        const double N = tensor_sum(0, tN);
+        const double M = tensor_sum(1, tM);
+        if (tid == 0) {
+            float a1 = (M > 0.0) ? (float)(N / M) : alpha0;
+            if (allzero) a1 = 1.0f;
+            s_alpha1 = a1;
+            *t.gscale = a1;
+        }
+        __syncthreads();
+        alpha1 = s_alpha1;
+    }
+    const float inv_alpha1 = __builtin_amdgcn_rcpf(alpha1);
+
+    // ---- Eq. 6, new assignment, Eq. 8 search, packing (k_search, per block)
+    double terr[kSmallPer];
+#pragma unroll
+    for (int k = 0; k < kSmallPer; ++k) {
+        terr[k] = 0.0;
+        const uint32_t i = (uint32_t)k * kSmallWG + tid;
+        if (i < t.nblk) {
+            float w[16], q[16];
+            uint32_t nib[2], out_code;
+            float out_err;
+            widen(k, w);
+            if (allzero) {
+                float x[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) x[j] = w[j];
+                nib[0] = fp4x8(x);
+                nib[1] = fp4x8(x + 8);
+                out_code = kE4M3Min;
+                out_err = 0.0f;
+            } else if constexpr (METHOD == SOAR_METHOD_RTN) {
+                uint32_t c0;
+                float delta0;
+                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                out_code = c0;
+                out_err = block_error(w, q, alpha0 * delta0);
+            } else {
+                const float delta_star = (rho[k] < 0.0f) ? -rho[k] : rho[k] / alpha1;
+                const int centre = (int)e4m3_project(delta_star);
+                assign_codes(w, alpha1 * delta_star, nib, q);
+                int best;
+                float best_err;
+                bool done = false;
+                if (!full_search) done = search_certified(w, q, alpha1, inv_alpha1, centre, radius, best, best_err);
+                if (!done) search_full(w, q, alpha1, centre, radius, best, best_err);
+                out_code = (uint32_t)best;
+                out_err = best_err;
+            }
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            u32x2 packed = {nib[0], nib[1]};
+            reinterpret_cast<u32x2 *>(t.codes)[i] = packed;
+            t.scales[i] = (uint8_t)out_code;
+            terr[k] = (double)out_err;
+        }
+    }
+    const double total = tensor_sum(2, terr);
+    if (tid == 0) {
+        if (t.sse) *t.sse = total;
+        if (t.status) *t.status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
+        if (METHOD == SOAR_METHOD_RTN) *t.gscale = allzero ? 1.0f : alpha0;
+    }
+}
+
 }  // namespace
