@@ -250,6 +250,45 @@ def test_stored_form_batch_equals_separate_calls_and_the_oracle():
     assert torch.equal(wide[:, :48], B.dequantize(qs[14], torch.bfloat16)) and bool((wide[:, 48:] == 7.0).all())
 
 
+def test_one_workgroup_kernel_for_small_tensors_and_its_boundary():
+    """A tensor of at most 4096 blocks handed over alone takes the one-workgroup kernel; a forced launch shape
+    takes the general path.  Both against the oracle and against each other: packed and strided, both element
+    types, both methods, the sizes on either side of the boundary, degenerate tensors."""
+    g = torch.Generator(device="cpu").manual_seed(4096)
+    cases = []
+    for rows, cols in ((256, 256), (257, 256), (255, 256), (64, 1024), (5, 48)):
+        f = torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g)) * 0.03
+        cases.append(f.to(torch.bfloat16).to(DEV))
+        cases.append((f * 1.0009765625).to(DEV))
+    pb = (torch.randn(60, 224, generator=g) * 0.1).to(torch.bfloat16).to(DEV)
+    pf = (torch.randn(60, 224, generator=g) * 0.1).to(DEV)
+    cases += [pb[:, 32:32 + 160], pf[:, 16:16 + 160]]
+    for w in cases:
+        for method, K in ((B.SOAR_METHOD_SOAR, 4), (B.SOAR_METHOD_SOAR, 0), (B.SOAR_METHOD_RTN, 0)):
+            what = f"{tuple(w.shape)} {w.dtype} stride {w.stride(0)} method {method} K {K}"
+            out, ref = check_against_oracle(w.contiguous(), method, K, what=what)
+            if not w.is_contiguous():                      # the strided view gives the bytes of its packed copy
+                packed, out = out, B.quantize(w, method, K)
+                torch.cuda.synchronize()
+                assert torch.equal(out.codes, packed.codes) and torch.equal(out.scales, packed.scales), what
+                assert out.global_scale.item() == packed.global_scale.item() and out.sse.item() == packed.sse.item(), what
+            other = B.quantize(w, method, K, B.SOAR_SEARCH_FULL, tiles_per_wg=1)
+            torch.cuda.synchronize()
+            assert torch.equal(out.codes, other.codes) and torch.equal(out.scales, other.scales), what
+            assert out.global_scale.item() == other.global_scale.item(), what
+            assert math.isclose(out.sse.item(), other.sse.item(), rel_tol=1e-12), what
+    z = torch.zeros(16, 64, dtype=torch.bfloat16, device=DEV)
+    z[3, 5] = -0.0
+    out = B.quantize(z, B.SOAR_METHOD_SOAR, 4)
+    bad = torch.ones(16, 64, device=DEV)
+    bad[2, 2] = float("nan")
+    out_bad = B.quantize(bad, B.SOAR_METHOD_SOAR, 4)
+    torch.cuda.synchronize()
+    assert int(out.status.item()) == B.SOAR_STATUS_ALLZERO and out.global_scale.item() == 1.0 and out.sse.item() == 0.0
+    assert bool((out.scales == 1).all()) and int(out.codes.view(-1)[3 * 32 + 2].item()) == 0x80
+    assert int(out_bad.status.item()) & B.SOAR_STATUS_NONFINITE
+
+
 # ----------------------------------------------------------------- degenerate inputs
 def test_extreme_magnitudes_and_subnormal_scales():
     g = torch.Generator(device="cpu").manual_seed(9)
