@@ -201,7 +201,8 @@ typedef struct {
  * model, Sec. 4.1) on one stream with one shared workspace of at least
  * soar_batch_workspace_bytes().  Consecutive tensors of one element type are
  * served by the same kernel launches (up to 8 tensors and 256 MiB of weights
- * per launch), each tensor with its own tensor-wide reductions; results are those
+ * per launch, 512 MiB where the maxima are supplied and one pass remains), each
+ * tensor with its own tensor-wide reductions; results are those
  * of n separate soar_quantize calls.  `descs` is HOST memory and is not
  * referenced after the call returns.  All descriptors are validated before
  * anything is enqueued.
@@ -339,7 +340,7 @@ typedef struct {
 /*
  * soar_mxfp4_quantize for n tensors on one stream with one workspace of at least
  * soar_mxfp4_batch_workspace_bytes(): up to 8 consecutive tensors of one element
- * type share a kernel launch; results are those of n separate calls.  `descs` is
+ * type (and at most 512 MiB of input) share a kernel launch; results are those of n separate calls.  `descs` is
  * HOST memory, not referenced after the call returns; all descriptors are
  * validated before anything is enqueued.
  */
