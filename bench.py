@@ -583,6 +583,26 @@ def bench_mxfp4(args, torch, B, synth, dev):
                         "avg_launch_us": kernels["mx"]["avg_us"],
                         "note": "per-launch HIP-event durations on the launch stream, single-stream pass, up to 8 tensors per launch"}
 
+    # the way back: soar_mxfp4_dequantize, one call per tensor, bf16 out (2 + 1/2 + 1/32 bytes per weight)
+    backs = [torch.empty((s.rows, s.cols), dtype=torch.bfloat16, device=dev) for s in specs]
+    st = torch.cuda.current_stream().cuda_stream
+
+    def back():
+        for s, o, b in zip(specs, outs, backs):
+            rc = B.soar_mxfp4_dequantize(o.codes.data_ptr(), o.scales.data_ptr(), s.rows, s.cols, B.SOAR_BF16, b.data_ptr(),
+                                         s.cols, st)
+            assert rc == B.SOAR_OK, rc
+    back()
+    torch.cuda.synchronize()
+    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    d0.record()
+    for _ in range(3):
+        back()
+    d1.record()
+    torch.cuda.synchronize()
+    deq_ms = d0.elapsed_time(d1) / 3
+    del backs
+
     # error of the plain conversion, for the ratio the paper's table is about
     p_plain = B.soar_mx_default_params(dss=False)
     step(p_plain)
@@ -612,7 +632,10 @@ def bench_mxfp4(args, torch, B, synth, dev):
                    "n_beta": p.n_beta if dss else None, "beta": [p.beta_lo, p.beta_hi] if dss else None,
                    "radius": p.radius if dss else None},
         "weights_per_s": E / (ms_per_step * 1e-3), "mse_vs_plain_mxfp4": sse / sse_plain if sse_plain > 0 else None,
-        "sse": sse, "sse_plain": sse_plain, "status_bits_or": status, "kernels": kernels, "roofline": roofline,
+        "sse": sse, "sse_plain": sse_plain, "status_bits_or": status,
+        "dequantize": {"entry_point": "soar_mxfp4_dequantize (one call per tensor, bf16 out)", "ms_per_step": deq_ms,
+                       "hbm_frac": 2.53125 * E / (deq_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "kernels": kernels, "roofline": roofline,
         "cpu_baseline": cpu}))
 
 
