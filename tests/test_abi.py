@@ -126,6 +126,38 @@ def test_stored_form_batch_host_side_argument_validation():
     assert int(B.lib().soar_dequantize_batch(-1, None, None)) == 2 and int(B.lib().soar_recon_error_batch(2, None, None)) == 1
 
 
+def test_header_is_plain_c_and_layouts_match_the_binding(tmp_path):
+    """include/soar.h through a C99 compiler in pedantic mode, linked against the library; the structure
+    sizes and offsets the C side prints are those of the ctypes structures; host validation from C."""
+    import subprocess
+    exe = str(tmp_path / "c_abi_check")
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+           "-I", os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_check.c"), "-o", exe,
+           "-L", lib_dir, "-lsoar_hip", "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib",
+           "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
+    r = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout
+    got = {}
+    for line in r.stdout.splitlines():
+        key, _, val = line.rpartition(" ")
+        got[key] = val
+    for name in ("soar_params", "soar_tensor_desc", "soar_stored_desc", "soar_mx_params", "soar_mx_tensor_desc"):
+        assert int(got["sizeof " + name]) == C.sizeof(getattr(B, name)), name
+    for name, field in (("soar_params", "dss_radius"), ("soar_params", "early_stop_rel"), ("soar_params", "streams"),
+                        ("soar_tensor_desc", "d_codes"), ("soar_tensor_desc", "d_amax_in"), ("soar_stored_desc", "dtype"),
+                        ("soar_stored_desc", "d_sse"), ("soar_mx_params", "radius"), ("soar_mx_params", "streams"),
+                        ("soar_mx_tensor_desc", "d_status")):
+        assert int(got[f"{name}.{field}"]) == getattr(getattr(B, name), field).offset, (name, field)
+    assert got["default iters 1 n_beta 1 block 16 struct_size"] == str(C.sizeof(B.soar_params))
+    assert int(got["version"]) == B.soar_version()
+    assert int(got["workspace 256x256"]) == B.soar_workspace_bytes(256, 256, B.soar_default_params())
+    assert got["null weights"] == "1" and got["empty batch"] == "0" and got["bad shape"] == "2"
+    assert r.stdout.splitlines()[-1].startswith("status text ") and len(r.stdout.splitlines()[-1]) > 14
+
+
 def test_product_path_has_no_cpu_route():
     torch = pytest.importorskip("torch")
     w = torch.zeros(16, 16, dtype=torch.bfloat16)
