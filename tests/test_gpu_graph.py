@@ -70,3 +70,58 @@ def test_batch_and_iterated_calls_replayed_from_a_graph():
                 _same(a, b)
                 if iters:
                     assert a.iters_run.item() == b.iters_run.item()
+
+
+def test_small_tensor_and_stored_form_calls_replayed_from_a_graph():
+    """The one-workgroup kernel of a small tensor, Eq. 3 and Eq. 4 (one-tensor and batch forms, the sums
+    cleared by a kernel) and the MXFP4 conversion in one captured sequence, replayed on new data."""
+    gen = torch.Generator(device=DEV).manual_seed(11)
+    small = (torch.randn(96, 256, generator=gen, device=DEV) * 0.05).to(torch.bfloat16)
+    big = (torch.randn(700, 1024, generator=gen, device=DEV) * 0.05)
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, 4)
+    outs = [B.new_outputs(96, 256, DEV), B.new_outputs(700, 1024, DEV)]
+    wss = [B.new_workspace(96, 256, p, DEV), B.new_workspace(700, 1024, p, DEV)]
+    backs = [torch.empty(96, 256, dtype=torch.bfloat16, device=DEV), torch.empty(700, 1024, dtype=torch.float32, device=DEV)]
+    sses = torch.empty(3, dtype=torch.float64, device=DEV)
+    mp = B.soar_mx_default_params(n_beta=9, streams=1)
+    mx_out = B.mx_new_outputs(96, 256, DEV)
+    mx_ws = torch.empty(B.soar_mxfp4_workspace_bytes(96, 256, mp), dtype=torch.uint8, device=DEV)
+    st = lambda: torch.cuda.current_stream().cuda_stream
+
+    def sequence():
+        for w, o, ws in zip((small, big), outs, wss):
+            B.quantize(w, workspace=ws, out=o)
+        descs = [B.stored_desc(o, w=w, out=b, sse=sses[k:k + 1]) for k, (w, o, b) in enumerate(zip((small, big), outs, backs))]
+        assert B.soar_recon_error_batch(descs, st()) == 0
+        assert B.soar_dequantize_batch(descs, st()) == 0
+        assert B.soar_recon_error(small.data_ptr(), B.SOAR_BF16, 96, 256, 256, outs[0].codes.data_ptr(),
+                                  outs[0].scales.data_ptr(), outs[0].global_scale.data_ptr(), sses[2:3].data_ptr(), st()) == 0
+        B.mx_quantize(small, mp, mx_ws, mx_out)
+
+    sequence()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        sequence()
+    for rep in range(4):
+        small.copy_((torch.randn(small.shape, generator=gen, device=DEV) * (0.02 * (rep + 1))).to(torch.bfloat16))
+        big.copy_(torch.randn(big.shape, generator=gen, device=DEV) * (0.03 * (rep + 1)))
+        for o in outs:
+            o.codes.zero_(); o.scales.zero_(); o.sse.zero_()
+        sses.fill_(-1.0)
+        for b in backs:
+            b.zero_()
+        mx_out.codes.zero_(); mx_out.scales.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for k, (w, o, b) in enumerate(zip((small, big), outs, backs)):
+            eager = B.quantize(w)
+            torch.cuda.synchronize()
+            _same(o, eager)
+            assert torch.equal(b, B.dequantize(eager, b.dtype))
+            assert abs(sses[k].item() - eager.sse.item()) <= 1e-9 * eager.sse.item()
+        assert abs(sses[2].item() - outs[0].sse.item()) <= 1e-9 * outs[0].sse.item()
+        mx_eager = B.mx_quantize(small, mp)
+        torch.cuda.synchronize()
+        assert torch.equal(mx_out.codes, mx_eager.codes) and torch.equal(mx_out.scales, mx_eager.scales)
+        assert mx_out.sse.item() == mx_eager.sse.item()
