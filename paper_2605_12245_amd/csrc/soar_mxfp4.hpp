@@ -79,6 +79,61 @@ __device__ __forceinline__ int mx_candidate(int e0, int c)
     return (c & 1) ? max(e0 - o, 0) : min(e0 + o, 254);
 }
 
+// Least Eq. 8 error over the stored codes e0-K..e0+K for fixed element codes q.  For fixed codes the
+// exact error is a parabola in the scale, f(x) = A - 2Bx + Cx^2 with B = sum w q, C = sum q^2 and
+// minimiser x* = B/C, and f(2x) < f(x) exactly when x* > 1.5 x: the power of two nearest to x* in
+// that sense, clamped to the window, is the winner, and only its error chain is evaluated -- provided
+// that x* stays clear of the two decision points next to it by a margin far above the rounding error
+// of the computed B/C, and that the exact rise to either neighbour, C x |3x - 2x*|, exceeds the
+// worst-case rounding error of the binary32 chains (34 ulp relative, all terms non-negative) by a
+// wide factor; candidates further out lie higher still (the bound grows with the rise).  Where that
+// cannot be shown for some lane of the wave, the other candidates are evaluated too, as the definition
+// says: the result never depends on the shortcut.
+__device__ __forceinline__ float mx_window_min(const float w[32], const float q[32], int e0, int radius)
+{
+    bool sure = false;
+    float m = 0.0f;
+    int cw = e0;
+    {
+        float B = 0.0f, C = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            B = __builtin_fmaf(w[j], q[j], B);
+            C = __builtin_fmaf(q[j], q[j], C);
+        }
+        const int lo = max(e0 - radius, 0), hi = min(e0 + radius, 254);
+        const float xstar = B * __builtin_amdgcn_rcpf(C);
+        // 0.75 * 2^(c-127) < x* <= 1.5 * 2^(c-127)  <=>  c = biased exponent of x* * 4/3 (approximately: checked below)
+        cw = (int)(__float_as_uint(xstar * 1.33333337f) >> 23);
+        cw = min(max(cw, lo), hi);
+        const float xw = e8m0_value(cw);
+        m = mx_block_error(w, q, xw);
+        // magnitudes at which squares underflow, or overflow, are left to the full evaluation
+        sure = C > 0.0f && B > 0x1p-100f && m > 0x1p-100f && m < 0x1p100f && xstar < 0x1p100f && cw >= 2 && cw <= 252;
+        const float clear = 0x1p-14f * xstar;       // the computed x* is within 2^-18.8 of the exact one
+        if (cw > lo) {
+            const float x = 0.5f * xw;
+            const float g = 2.0f * xstar - 3.0f * x;
+            const float rise = C * x * g;
+            sure = sure && g > clear && 0.8f * rise > 0x1p-16f * (m + rise);
+        }
+        if (cw < hi) {
+            const float g = 3.0f * xw - 2.0f * xstar;
+            const float rise = C * xw * g;
+            sure = sure && g > clear && 0.8f * rise > 0x1p-16f * (m + rise);
+        }
+    }
+    if (__builtin_amdgcn_ballot_w64(!sure) != 0ull) {
+        // the 2K other codes of the window (cw is one of them; a code clamped onto [0, 254] repeats another)
+        for (int t = 0; t < 2 * radius; ++t) {
+            int c = e0 - radius + t;
+            c += c >= cw ? 1 : 0;
+            m = fminf(m, mx_block_error(w, q, e8m0_value(min(max(c, 0), 254))));
+        }
+    }
+    return m;
+}
+
 template <bool FAST>
 __device__ __forceinline__ void mx_search(const float w[32], int e0, const float *s_beta, int n_beta, int radius,
                                           float &best_err, int &best_code, uint32_t best_nib[4], float q[32])
@@ -90,8 +145,7 @@ __device__ __forceinline__ void mx_search(const float w[32], int e0, const float
     for (int kb = 0; kb < n_beta; ++kb) {
         const float bk = s_beta[kb];
         mx_assign<FAST>(w, x0 * bk, nib, q);
-        float m = mx_block_error(w, q, x0);
-        for (int c = 1; c <= 2 * radius; ++c) m = fminf(m, mx_block_error(w, q, e8m0_value(mx_candidate(e0, c))));
+        const float m = mx_window_min(w, q, e0, radius);
         best_beta = (m < best) ? bk : best_beta;             // strictly better only: the first factor keeps a tie
         best = fminf(best, m);
     }
@@ -151,8 +205,7 @@ __device__ __forceinline__ void mx_search_two_pass(const float w[32], int e0, co
         if (j < n) {
             const float bk = s_beta[list[j * kWG + threadIdx.x]];
             mx_assign<FAST>(w, x0 * bk, nib, q);
-            float m = mx_block_error(w, q, x0);
-            for (int c = 1; c <= 2 * radius; ++c) m = fminf(m, mx_block_error(w, q, e8m0_value(mx_candidate(e0, c))));
+            const float m = mx_window_min(w, q, e0, radius);
             best_beta = (m < best) ? bk : best_beta;
             best = fminf(best, m);
         }
