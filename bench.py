@@ -32,6 +32,10 @@ BYTES_ABSMAX = 2.0
 SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2605 + 0.5806
 # the same for the one-pass plain NVFP4 with a supplied maximum (profiles/config4_rtn_amax.md)
 RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0010 + 0.5778
+# the same for the other one-pass kernels (profiles/config4_one_pass_kernels_hbm_traffic_pmc.md)
+MX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0011 + 0.5416
+DEQUANT_TRAFFIC_PER_WEIGHT_CONFIG4 = 0.5628 + 2.0002
+RECON_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.5645 + 0.0005
 # Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
 # method needs 16 products w*r, 16 roundings onto E2M1, 16 decoded values and, per stored-scale
 # candidate, 16 residuals (one fused op each) and 16 fused square-accumulates.
@@ -476,8 +480,11 @@ def bench_stored_form(args, torch, B, synth, dev):
         B.soar_kernel_timing_enable(False)
         kernels[kname[2:]] = {"launches": n, "total_ms": ms, "avg_us": ms / n * 1e3, "ms_per_step": ms / n_prof}
         gbs = per_w * E * n_prof / (ms * 1e-3) / 1e9
+        traffic = None
+        if args.workload == 4 and not args.layers and args.dtype == "bf16":
+            traffic = (DEQUANT_TRAFFIC_PER_WEIGHT_CONFIG4 if deq else RECON_TRAFFIC_PER_WEIGHT_CONFIG4) * E / (n / n_prof)
         roofline = {"kernel": kname, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_weight": per_w,
                     "weights_per_launch": E / (n / n_prof), "avg_launch_us": ms / n * 1e3,
                     "note": "per-launch HIP-event durations on the launch stream, "
                             + ("one launch per tensor" if one_by_one else "up to 8 tensors per launch")
@@ -577,8 +584,11 @@ def bench_mxfp4(args, torch, B, synth, dev):
         else:
             per_w = 2.0 + 0.5 + 1.0 / 32.0
             gbs = per_w * E / t_mx / 1e9
+            traffic = None
+            if args.workload == 4 and not args.layers:
+                traffic = MX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels["mx"]["launches"] / n_prof)
             roofline = {"kernel": "k_mx", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight": per_w,
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_weight": per_w,
                         "weights_per_launch": E / (kernels["mx"]["launches"] / n_prof),
                         "avg_launch_us": kernels["mx"]["avg_us"],
                         "note": "per-launch HIP-event durations on the launch stream, single-stream pass, up to 8 tensors per launch"}
