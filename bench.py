@@ -593,15 +593,15 @@ def bench_mxfp4(args, torch, B, synth, dev):
                         "avg_launch_us": kernels["mx"]["avg_us"],
                         "note": "per-launch HIP-event durations on the launch stream, single-stream pass, up to 8 tensors per launch"}
 
-    # the way back: soar_mxfp4_dequantize, one call per tensor, bf16 out (2 + 1/2 + 1/32 bytes per weight)
+    # the way back: soar_mxfp4_dequantize_batch, bf16 out (2 + 1/2 + 1/32 bytes per weight)
     backs = [torch.empty((s.rows, s.cols), dtype=torch.bfloat16, device=dev) for s in specs]
     st = torch.cuda.current_stream().cuda_stream
 
+    back_descs = [B.mx_stored_desc(o, b) for o, b in zip(outs, backs)]
+
     def back():
-        for s, o, b in zip(specs, outs, backs):
-            rc = B.soar_mxfp4_dequantize(o.codes.data_ptr(), o.scales.data_ptr(), s.rows, s.cols, B.SOAR_BF16, b.data_ptr(),
-                                         s.cols, st)
-            assert rc == B.SOAR_OK, rc
+        rc = B.soar_mxfp4_dequantize_batch(back_descs, st)
+        assert rc == B.SOAR_OK, rc
     back()
     torch.cuda.synchronize()
     d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -643,7 +643,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
                    "radius": p.radius if dss else None},
         "weights_per_s": E / (ms_per_step * 1e-3), "mse_vs_plain_mxfp4": sse / sse_plain if sse_plain > 0 else None,
         "sse": sse, "sse_plain": sse_plain, "status_bits_or": status,
-        "dequantize": {"entry_point": "soar_mxfp4_dequantize (one call per tensor, bf16 out)", "ms_per_step": deq_ms,
+        "dequantize": {"entry_point": "soar_mxfp4_dequantize_batch (bf16 out)", "ms_per_step": deq_ms,
                        "hbm_frac": 2.53125 * E / (deq_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "kernels": kernels, "roofline": roofline,
         "cpu_baseline": cpu}))

@@ -356,6 +356,12 @@ soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scale
                                   int64_t cols, soar_dtype out_dtype, void *d_out, int64_t ld_elems,
                                   void *hip_stream);
 
+/* The same for n stored tensors in a handful of launches (up to 8 tensors of one element type
+ * per launch): soar_stored_desc with d_codes (16-byte aligned), d_scales (E8M0 bytes), rows, cols
+ * (a multiple of 32), ld_elems, dtype and d_out; the other fields are not read.  The bytes are
+ * those of n one-tensor calls; errors are found before anything is enqueued. */
+soar_status soar_mxfp4_dequantize_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream);
+
 /*
  * The reciprocal used inside the iterated path's search loop (hardware estimate
  * plus one fused Newton step), exposed so that the claim it rests on can be

@@ -31,6 +31,7 @@ EXPORTS = (
     "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_rcp_midrange_f32",
     "soar_mx_default_params", "soar_mxfp4_workspace_bytes", "soar_mxfp4_quantize", "soar_mxfp4_dequantize",
+    "soar_mxfp4_dequantize_batch",
     "soar_mxfp4_quantize_batch", "soar_mxfp4_batch_workspace_bytes",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
 )
@@ -143,6 +144,8 @@ def lib():
     L.soar_mxfp4_batch_workspace_bytes.restype = C.c_size_t
     L.soar_mxfp4_dequantize.argtypes = [vp, vp, i64, i64, i32, vp, i64, vp]
     L.soar_mxfp4_dequantize.restype = i32
+    L.soar_mxfp4_dequantize_batch.argtypes = [i32, C.POINTER(soar_stored_desc), vp]
+    L.soar_mxfp4_dequantize_batch.restype = i32
     L.soar_rcp_midrange_f32.argtypes = [vp, i64, vp, vp]
     L.soar_rcp_midrange_f32.restype = i32
     L.soar_kernel_timing_enable.argtypes = [C.c_int]
@@ -305,6 +308,10 @@ def soar_recon_error_batch(descs: Sequence["soar_stored_desc"], hip_stream) -> i
 
 def soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream) -> int:
     return int(lib().soar_mxfp4_dequantize(d_codes, d_scales, rows, cols, out_dtype, d_out, ld_elems, hip_stream))
+
+
+def soar_mxfp4_dequantize_batch(descs: Sequence["soar_stored_desc"], hip_stream) -> int:
+    return int(lib().soar_mxfp4_dequantize_batch(len(descs), _stored_array(descs), hip_stream))
 
 
 def soar_rcp_midrange_f32(d_x, n, d_out, hip_stream) -> int:
@@ -576,6 +583,24 @@ def mx_quantize_batch(descs: Sequence[soar_mx_tensor_desc], params: soar_mx_para
     rc = soar_mxfp4_quantize_batch(descs, params, workspace.data_ptr(), workspace.numel(), _stream())
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_mxfp4_quantize_batch")
+
+
+def mx_stored_desc(q: Quantized, out: torch.Tensor) -> "soar_stored_desc":
+    rows, cols, ld = _check_matrix(out)
+    d = soar_stored_desc()
+    d.d_codes, d.d_scales = q.codes.data_ptr(), q.scales.data_ptr()
+    d.rows, d.cols, d.ld_elems, d.dtype = rows, cols, ld, _dtype_code(out)
+    d.d_out = out.data_ptr()
+    return d
+
+
+def mx_dequantize_batch(qs: Sequence[Quantized], out_dtype=torch.bfloat16) -> list:
+    """MXFP4 tensors back to bf16 / fp32 in a handful of launches."""
+    outs = [torch.empty((q.scales.shape[0], q.scales.shape[1] * 32), dtype=out_dtype, device=q.codes.device) for q in qs]
+    rc = soar_mxfp4_dequantize_batch([mx_stored_desc(q, o) for q, o in zip(qs, outs)], _stream())
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_mxfp4_dequantize_batch")
+    return outs
 
 
 def mx_dequantize(q: Quantized, out_dtype=torch.bfloat16) -> torch.Tensor:

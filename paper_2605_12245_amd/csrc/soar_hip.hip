@@ -837,28 +837,58 @@ soar_status soar_mxfp4_quantize(const void *d_w, soar_dtype dtype, int64_t rows,
     return soar_mxfp4_quantize_batch(1, &d, params, d_workspace, workspace_bytes, hip_stream);
 }
 
+soar_status soar_mxfp4_dequantize_batch(int32_t n, const soar_stored_desc *descs, void *hip_stream)
+{
+    if (n < 0) return SOAR_ERR_SHAPE;
+    if (n > 0 && !descs) return SOAR_ERR_NULL;
+    for (int32_t k = 0; k < n; ++k) {
+        const soar_stored_desc &d = descs[k];
+        if (!d.d_codes || !d.d_scales || !d.d_out) return SOAR_ERR_NULL;
+        if (d.dtype != SOAR_BF16 && d.dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
+        soar_status s = check_mx_shape(d.rows, d.cols, d.ld_elems);
+        if (s != SOAR_OK) return s;
+        s = check_matrix_ptr(d.d_out, d.dtype, d.ld_elems);
+        if (s != SOAR_OK) return s;
+        if (reinterpret_cast<uintptr_t>(d.d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    for (int32_t i = 0; i < n;) {
+        const int32_t j = stored_group_end(n, descs, i);
+        StoredBatch b;
+        std::memset(&b, 0, sizeof(b));
+        b.n = (uint32_t)(j - i);
+        uint32_t wg = 0;
+        for (int32_t k = i; k < j; ++k) {
+            const soar_stored_desc &d = descs[k];
+            StoredTask &t = b.t[k - i];
+            t.codes = d.d_codes; t.scales = d.d_scales; t.out = d.d_out;
+            t.ld = d.ld_elems;
+            t.bpr = (uint32_t)(d.cols / 32);
+            t.nblk = (uint32_t)(d.rows * (d.cols / 32));
+            t.contiguous = d.ld_elems == d.cols ? 1u : 0u;
+            t.n_wg = (t.nblk + kWG - 1) / kWG;
+            t.wg_begin = wg;
+            wg += t.n_wg;
+        }
+        ScopedTimer tm(SOAR_KERNEL_DEQUANT, st);
+        if (descs[i].dtype == SOAR_BF16) hipLaunchKernelGGL(k_mx_dequant<SOAR_BF16>, dim3(wg), dim3(kWG), 0, st, b);
+        else hipLaunchKernelGGL(k_mx_dequant<SOAR_FP32>, dim3(wg), dim3(kWG), 0, st, b);
+        SOAR_LAUNCH_CHECK();
+        i = j;
+    }
+    return SOAR_OK;
+}
+
 soar_status soar_mxfp4_dequantize(const uint8_t *d_codes, const uint8_t *d_scales, int64_t rows, int64_t cols,
                                   soar_dtype out_dtype, void *d_out, int64_t ld_elems, void *hip_stream)
 {
-    if (!d_codes || !d_scales || !d_out) return SOAR_ERR_NULL;
-    if (out_dtype != SOAR_BF16 && out_dtype != SOAR_FP32) return SOAR_ERR_DTYPE;
-    soar_status s = check_mx_shape(rows, cols, ld_elems);
-    if (s != SOAR_OK) return s;
-    s = check_matrix_ptr(d_out, out_dtype, ld_elems);
-    if (s != SOAR_OK) return s;
-    if (reinterpret_cast<uintptr_t>(d_codes) % 16 != 0) return SOAR_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const uint32_t nblk = (uint32_t)(rows * (cols / 32));
-    const uint32_t grid = (nblk + kWG - 1) / kWG;
-    ScopedTimer tm(SOAR_KERNEL_DEQUANT, st);
-    if (out_dtype == SOAR_BF16)
-        hipLaunchKernelGGL(k_mx_dequant<SOAR_BF16>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, nblk,
-                           (uint32_t)(cols / 32), ld_elems, ld_elems == cols ? 1u : 0u, d_out);
-    else
-        hipLaunchKernelGGL(k_mx_dequant<SOAR_FP32>, dim3(grid), dim3(kWG), 0, st, d_codes, d_scales, nblk,
-                           (uint32_t)(cols / 32), ld_elems, ld_elems == cols ? 1u : 0u, d_out);
-    SOAR_LAUNCH_CHECK();
-    return SOAR_OK;
+    soar_stored_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.d_codes = d_codes; d.d_scales = d_scales;
+    d.rows = rows; d.cols = cols; d.ld_elems = ld_elems;
+    d.dtype = out_dtype;
+    d.d_out = d_out;
+    return soar_mxfp4_dequantize_batch(1, &d, hip_stream);
 }
 
 soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, void *hip_stream)

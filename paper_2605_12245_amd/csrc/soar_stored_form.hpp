@@ -1,7 +1,8 @@
-// Kernels on the stored NVFP4 form: k_dequant (Eq. 3), k_recon (Eq. 4), and the element-wise
-// format kernels the tests use.
+// Kernels on the stored forms: k_dequant (Eq. 3), k_recon (Eq. 4), k_mx_dequant (MXFP4), and the
+// element-wise format kernels the tests use.
 #pragma once
 #include "soar_device.hpp"
+#include "soar_mxfp4.hpp"        // e8m0_value
 
 namespace {
 
@@ -82,6 +83,70 @@ __global__ __launch_bounds__(kWG) void k_dequant(const StoredBatch batch)
         float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(g.out) + off);
 #pragma unroll
         for (int k = 0; k < 4; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
+    }
+}
+
+// MXFP4: w^ = q * 2^(e-127) per block of 32 (bpr counts blocks of 32; gscale is unused)
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_mx_dequant(const StoredBatch batch)
+{
+    constexpr int kP = pieces_per_block<DT, 32>();
+    __shared__ u32x4 s_x[kWG * kP];                    // store_wave_blocks: one region per wave
+    uint32_t lwg;
+    const StoredTask g = batch.t[find_task(batch, lwg)];
+    const uint8_t *codes = g.codes, *scales = g.scales;
+    const uint32_t nblk = g.nblk, bpr = g.bpr, contiguous = g.contiguous;
+    const int64_t ld = g.ld;
+    void *out = g.out;
+    const uint32_t i = lwg * kWG + threadIdx.x;
+    const uint32_t wave_first = i - (threadIdx.x & 63u);
+    if (wave_first >= nblk) return;
+    const bool inside = i < nblk;
+    const uint32_t e = inside ? (uint32_t)__builtin_nontemporal_load(scales + i) : 127u;
+    const bool skip = e == 255u;                        // not a scale: the block's output is left alone
+    float v[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) v[j] = 0.0f;
+    if (inside && !skip) {
+        const float s = e8m0_value((int)e);
+        const u32x4 nb = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(codes) + i);
+        fp4x8_values(nb.x, v);
+        fp4x8_values(nb.y, v + 8);
+        fp4x8_values(nb.z, v + 16);
+        fp4x8_values(nb.w, v + 24);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) v[j] = v[j] * s;
+    }
+    // packed rows: the wave writes its 64 blocks in coalesced pieces, unless one of them is to be skipped
+    if (contiguous && __builtin_amdgcn_ballot_w64(skip) == 0ull) {
+        store_wave_blocks<DT, 32>(out, wave_first, nblk, s_x + (threadIdx.x >> 6) * (64 * kP), v);
+        return;
+    }
+    if (!inside || skip) return;
+    size_t off;
+    if (contiguous) {
+        off = (size_t)i * 32;
+    } else {
+        const uint32_t row = i / bpr;
+        off = (size_t)row * (size_t)ld + (size_t)(i - row * bpr) * 32;
+    }
+    if constexpr (DT == SOAR_BF16) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        typedef float f2 __attribute__((ext_vector_type(2)));
+        uint32_t u[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            f2 in = {v[2 * k], v[2 * k + 1]};
+            bf2 o = __builtin_convertvector(in, bf2);     // round to nearest even
+            __builtin_memcpy(&u[k], &o, 4);
+        }
+        uint4 *p = reinterpret_cast<uint4 *>(static_cast<uint16_t *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = make_uint4(u[4 * k], u[4 * k + 1], u[4 * k + 2], u[4 * k + 3]);
+    } else {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(out) + off);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p[k] = make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]);
     }
 }
 

@@ -124,6 +124,11 @@ def test_stored_form_batch_host_side_argument_validation():
         assert call([desc(d_codes=0x2004)], 0) == 7
     assert B.soar_recon_error_batch([desc(d_sse=0)], 0) == 1
     assert int(B.lib().soar_dequantize_batch(-1, None, None)) == 2 and int(B.lib().soar_recon_error_batch(2, None, None)) == 1
+    # the MXFP4 form reads codes, scales, shape, type and output only
+    assert B.soar_mxfp4_dequantize_batch([], 0) == 0
+    assert B.soar_mxfp4_dequantize_batch([desc(d_codes=0x10, d_out=0)], 0) == 1
+    assert B.soar_mxfp4_dequantize_batch([desc(d_codes=0x10, cols=48, ld_elems=48)], 0) == 2
+    assert B.soar_mxfp4_dequantize_batch([desc(d_codes=0x8)], 0) == 7 and B.soar_mxfp4_dequantize_batch([desc(d_codes=0x10, dtype=4)], 0) == 3
 
 
 def test_header_is_plain_c_and_layouts_match_the_binding(tmp_path):

@@ -132,6 +132,13 @@ def test_dequantize_ragged_waves_and_a_byte_that_is_no_scale(rows, cols):
         back = B.mx_dequantize(q, dt).cpu()
         got = back.view(torch.int16).numpy().view(np.uint16) if dt == torch.bfloat16 else back.numpy()
         assert np.array_equal(got, oracle.mxfp4_dequantize(codes, scales, odt))
+    # the batch form: this tensor twice (both output types) and a strided output, the bytes of one-tensor calls
+    wide = torch.full((rows, cols + 64), 3.0, dtype=torch.bfloat16, device=DEV)
+    b16, b32 = B.mx_dequantize_batch([q], torch.bfloat16)[0], B.mx_dequantize_batch([q, q], torch.float32)[1]
+    assert B.soar_mxfp4_dequantize_batch([B.mx_stored_desc(q, wide[:, :cols])], 0) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(b16, B.mx_dequantize(q, torch.bfloat16)) and torch.equal(b32, B.mx_dequantize(q, torch.float32))
+    assert torch.equal(wide[:, :cols], b16) and bool((wide[:, cols:] == 3.0).all())
     flat = scales.reshape(-1)
     flat[:: max(1, flat.size // 5)] = 255
     d_scales = torch.from_numpy(scales).to(DEV)
