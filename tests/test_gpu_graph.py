@@ -125,3 +125,32 @@ def test_small_tensor_and_stored_form_calls_replayed_from_a_graph():
         torch.cuda.synchronize()
         assert torch.equal(mx_out.codes, mx_eager.codes) and torch.equal(mx_out.scales, mx_eager.scales)
         assert mx_out.sse.item() == mx_eager.sse.item()
+
+
+def test_two_callers_on_two_streams_share_the_internal_stream():
+    """Two batches enqueued back to back on two caller streams (each with its own workspace and
+    outputs) both use the library's one internal stream for their second lane: the fork / join events
+    keep each ordered, and the results are those of running them one after the other."""
+    specs = synth.workload_specs(4, 8)
+    wa = [synth.make_weight(s, DEV) for s in specs[:21]]
+    wb = [synth.make_weight(s, DEV) for s in specs[21:42]]
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, 4)
+    ref_a, ref_b = B.quantize_tensors(wa, p), B.quantize_tensors(wb, p)
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        with torch.cuda.stream(sa):
+            out_a = B.quantize_tensors(wa, p)
+            mx_a = [B.mx_quantize(w, B.soar_mx_default_params(n_beta=5)) for w in wa[:3]]
+        with torch.cuda.stream(sb):
+            out_b = B.quantize_tensors(wb, p)
+            err_b = B.recon_error_batch(wb, out_b)
+        torch.cuda.synchronize()
+        for a, r in zip(out_a + out_b, ref_a + ref_b):
+            _same(a, r)
+        for k, r in enumerate(ref_b):
+            assert abs(err_b[k].item() - r.sse.item()) <= 1e-9 * r.sse.item()
+        for w, m in zip(wa[:3], mx_a):
+            again = B.mx_quantize(w, B.soar_mx_default_params(n_beta=5))
+            torch.cuda.synchronize()
+            assert torch.equal(m.codes, again.codes) and torch.equal(m.scales, again.scales)
