@@ -13,6 +13,7 @@
 
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 
 #define CHECK(x)                                                       \
     do {                                                               \
@@ -164,14 +165,28 @@ int write_case(const char *name, const Buffers &b, uint32_t units)
 
 }  // namespace
 
-int main()
+int main(int argc, char **argv)
 {
-    const size_t read_bytes = (size_t)434 << 20;      // multiple of 256 lanes x 128 bytes
+    // optional argument: MiB read per launch (default 434; a multiple of 32 KiB); beyond the 256 MiB last-level
+    // cache plus what one repetition leaves behind, every read comes from HBM
+    const size_t read_bytes = (size_t)(argc > 1 ? atol(argv[1]) : 434) << 20;
     const uint32_t write_units = 12u << 20;           // blocks of 16 weights: 384 MiB of bf16 out, 768 MiB of fp32
+    if (read_bytes == 0 || read_bytes % ((size_t)kWG * 128) != 0 || read_bytes > ((size_t)8 << 30)) {
+        std::printf("size: a multiple of 32 KiB, at most 8 GiB\n");
+        return 1;
+    }
+    // the read cases with stores write read_bytes / 4 of `out` and read_bytes / 32 of `small`;
+    // the write cases write write_units * 64 of `out` and read write_units of `small` and 8 * write_units of `in`
+    const size_t out_bytes = read_bytes / 4 > (size_t)write_units * 64 ? read_bytes / 4 : (size_t)write_units * 64;
+    const size_t small_bytes = read_bytes / 32 > write_units ? read_bytes / 32 : write_units;
+    if (read_bytes < (size_t)write_units * 8) {
+        std::printf("size: at least %zu MiB\n", ((size_t)write_units * 8) >> 20);
+        return 1;
+    }
     Buffers b;
     CHECK(hipMalloc(&b.in, read_bytes));
-    CHECK(hipMalloc(&b.out, (size_t)write_units * 64));
-    CHECK(hipMalloc(&b.small, read_bytes / 32 > write_units ? read_bytes / 32 : write_units));
+    CHECK(hipMalloc(&b.out, out_bytes));
+    CHECK(hipMalloc(&b.small, small_bytes));
     CHECK(hipMalloc(&b.sink, 4));
     CHECK(hipMemset(b.in, 1, read_bytes));
     CHECK(hipMemset(b.small, 2, write_units));
