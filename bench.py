@@ -26,16 +26,36 @@ BYTES_3PASS = 6.5625           # per bf16 weight: three reads + codes + scales
 BYTES_SEARCH = 2.5625          # search kernel alone: one read + codes + scales
 BYTES_STATS = 2.0
 BYTES_ABSMAX = 2.0
-# HBM bytes per weight the search kernel really moves on the full-model workload, from
-# rocprofv3 FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size
-# (profiles/config4_hbm_traffic_pmc.md): 2.2605 read + 0.5805 written.
-SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.2605 + 0.5806
-# the same for the one-pass plain NVFP4 with a supplied maximum (profiles/config4_rtn_amax.md)
-RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0010 + 0.5778
-# the same for the other one-pass kernels (profiles/config4_one_pass_kernels_hbm_traffic_pmc.md)
-MX_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.0011 + 0.5416
-DEQUANT_TRAFFIC_PER_WEIGHT_CONFIG4 = 0.5628 + 2.0002
-RECON_TRAFFIC_PER_WEIGHT_CONFIG4 = 2.5645 + 0.0005
+# HBM bytes per weight that a kernel really moves, and vector instructions it really executes, come from
+# rocprofv3 counter runs (FETCH_SIZE / WRITE_SIZE scaled by a plain copy of known size; SQ_INSTS_VALU): the
+# figures live in profiles/pmc_table.json, one entry per (algorithm, workload, dtype, kernel), beside the
+# summaries they were taken from.  No entry, no figure: the JSON line then carries null and says why.
+PMC_TABLE = os.path.join(ROOT, "profiles", "pmc_table.json")
+
+
+def pmc_entry(algorithm, workload, dtype, kernel, layers=0, search="auto"):
+    """-> (entry or None, reason)"""
+    if layers:
+        return None, "measured on the whole workload only, not on a --layers subset"
+    try:
+        with open(PMC_TABLE) as f:
+            table = json.load(f)
+    except (OSError, ValueError) as e:
+        return None, f"{os.path.relpath(PMC_TABLE, ROOT)} not readable ({e.__class__.__name__})"
+    for e in table.get("entries", []):
+        if (e["algorithm"], e["workload"], e["dtype"], e["kernel"], e.get("search", "auto")) == \
+                (algorithm, f"config{workload}", dtype, kernel, search):
+            return e, e.get("source", "")
+    return None, f"no counter run recorded for ({algorithm}, config{workload}, {dtype}, {kernel}, search {search})"
+
+
+def traffic_per_launch(algorithm, workload, dtype, kernel, weights_per_launch, layers=0):
+    e, why = pmc_entry(algorithm, workload, dtype, kernel, layers)
+    if e is None or "read_B_per_weight" not in e:
+        return None, why
+    return (e["read_B_per_weight"] + e["written_B_per_weight"]) * weights_per_launch, why
+
+
 # Iterated path (--algorithm paper): arithmetic-bound.  Per block, factor beta and iteration the
 # method needs 16 products w*r, 16 roundings onto E2M1, 16 decoded values and, per stored-scale
 # candidate, 16 residuals (one fused op each) and 16 fused square-accumulates.
@@ -74,7 +94,7 @@ def parse_args():
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
     ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax", "mxfp4", "mxfp4-dss",
-                                               "dequantize", "recon-error"],
+                                               "dequantize", "recon-error", "copy-calibration"],
                     default="single-step",
                     help="single-step: Algorithm 1 with T = 1, beta = {1} (the headline path); "
                          "paper: T = 15, 101 beta factors, bracket candidates, early stop 1e-3; "
@@ -82,7 +102,9 @@ def parse_args():
                          "rtn: plain NVFP4 (two passes); "
                          "rtn-amax: plain NVFP4 with each tensor's maximum supplied (one pass); "
                          "mxfp4 / mxfp4-dss: MXFP4 conversion, plain or with the decoupled scale search; "
-                         "dequantize / recon-error: Eq. 3 / Eq. 4 on the stored form of every tensor (one call per tensor)")
+                         "dequantize / recon-error: Eq. 3 / Eq. 4 on the stored form of every tensor (one call per tensor); "
+                         "copy-calibration: no quantization at all -- a plain 1 GiB device copy, five times, whose known "
+                         "traffic scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
     ap.add_argument("--dtype", choices=["bf16", "fp32"], default="bf16",
@@ -116,6 +138,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     B.lib()
+
+    if args.algorithm == "copy-calibration":
+        return copy_calibration(torch, dev)
 
     if args.algorithm in ("mxfp4", "mxfp4-dss"):
         if args.dtype != "bf16":
@@ -290,13 +315,10 @@ def main():
         dom = max(("absmax", "stats", "search", "small"), key=lambda k: kernels[k]["total_ms"])
         kernels = {k: v for k, v in kernels.items() if v["launches"]}
         achieved = kernels[dom]["GBps"]
-        traffic = None
-        if dom == "search" and args.workload == 4 and not args.layers and not rtn_amax and args.dtype == "bf16":
-            traffic = SEARCH_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
-        if args.algorithm == "rtn-amax" and args.workload == 4 and not args.layers and args.dtype == "bf16":
-            traffic = RTN_AMAX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels[dom]["launches"] / n_prof)
+        traffic, traffic_source = traffic_per_launch(args.algorithm, args.workload, args.dtype, "k_" + dom,
+                                                     E / (kernels[dom]["launches"] / n_prof), args.layers)
         roofline = {"kernel": "k_" + dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                     "algorithmic_bytes_per_weight": per_elem[dom],
                     "weights_per_launch": E / (kernels[dom]["launches"] / n_prof),
                     "avg_launch_us": kernels[dom]["avg_us"],
@@ -411,6 +433,26 @@ def main():
     print(json.dumps(out))
 
 
+def copy_calibration(torch, dev, gib=1.0, reps=5):
+    """A dtype-preserving element-wise copy (torch's vectorized kernel): 1 GiB read and 1 GiB written per
+    dispatch.  Under `rocprofv3 --pmc FETCH_SIZE` (then WRITE_SIZE) its counter values per dispatch, against
+    the 1 048 576 KiB really moved, give the scale factors of those counters."""
+    n = int(gib * (1 << 30)) // 4
+    src = torch.arange(n, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        torch.add(src, 0, out=dst)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    print(json.dumps({"metric": "copy_calibration", "bytes_read_per_dispatch": n * 4, "bytes_written_per_dispatch": n * 4,
+                      "dispatches": reps, "ms_per_dispatch": ms, "GBps_read_plus_written": 2 * n * 4 / (ms * 1e-3) / 1e9,
+                      "kernel": "torch vectorized_elementwise_kernel"}))
+
+
 def bench_stored_form(args, torch, B, synth, dev):
     """Eq. 3 (soar_dequantize_batch) or Eq. 4 (soar_recon_error_batch) over every tensor of the workload, on
     the stored form the single-step path produced; --per-tensor: one soar_dequantize / soar_recon_error call
@@ -480,11 +522,10 @@ def bench_stored_form(args, torch, B, synth, dev):
         B.soar_kernel_timing_enable(False)
         kernels[kname[2:]] = {"launches": n, "total_ms": ms, "avg_us": ms / n * 1e3, "ms_per_step": ms / n_prof}
         gbs = per_w * E * n_prof / (ms * 1e-3) / 1e9
-        traffic = None
-        if args.workload == 4 and not args.layers and args.dtype == "bf16":
-            traffic = (DEQUANT_TRAFFIC_PER_WEIGHT_CONFIG4 if deq else RECON_TRAFFIC_PER_WEIGHT_CONFIG4) * E / (n / n_prof)
+        traffic, traffic_source = traffic_per_launch(args.algorithm, args.workload, args.dtype, kname, E / (n / n_prof), args.layers)
         roofline = {"kernel": kname, "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_weight": per_w,
+                    "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                    "algorithmic_bytes_per_weight": per_w,
                     "weights_per_launch": E / (n / n_prof), "avg_launch_us": ms / n * 1e3,
                     "note": "per-launch HIP-event durations on the launch stream, "
                             + ("one launch per tensor" if one_by_one else "up to 8 tensors per launch")
@@ -584,11 +625,11 @@ def bench_mxfp4(args, torch, B, synth, dev):
         else:
             per_w = 2.0 + 0.5 + 1.0 / 32.0
             gbs = per_w * E / t_mx / 1e9
-            traffic = None
-            if args.workload == 4 and not args.layers:
-                traffic = MX_TRAFFIC_PER_WEIGHT_CONFIG4 * E / (kernels["mx"]["launches"] / n_prof)
+            traffic, traffic_source = traffic_per_launch(args.algorithm, args.workload, "bf16", "k_mx",
+                                                         E / (kernels["mx"]["launches"] / n_prof), args.layers)
             roofline = {"kernel": "k_mx", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "algorithmic_bytes_per_weight": per_w,
+                        "frac": gbs / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                        "algorithmic_bytes_per_weight": per_w,
                         "weights_per_launch": E / (kernels["mx"]["launches"] / n_prof),
                         "avg_launch_us": kernels["mx"]["avg_us"],
                         "note": "per-launch HIP-event durations on the launch stream, single-stream pass, up to 8 tensors per launch"}

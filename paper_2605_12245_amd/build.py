@@ -1,6 +1,4 @@
-"""Build the HIP library (gfx950) into paper_2605_12245_amd/libsoar_hip.so, and the two
-stand-alone probes (instruction cost, access patterns) into paper_2605_12245_amd/valu_probe
-and paper_2605_12245_amd/access_probe."""
+"""Build the HIP library (gfx950) into paper_2605_12245_amd/libsoar_hip.so."""
 import os
 import subprocess
 import sys
@@ -9,10 +7,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRC = os.path.join(HERE, "csrc", "soar_hip.hip")
 OUT = os.path.join(HERE, "libsoar_hip.so")
-PROBE_SRC = os.path.join(HERE, "csrc", "valu_probe.hip")
-PROBE_OUT = os.path.join(HERE, "valu_probe")
-PROBES = [(PROBE_SRC, PROBE_OUT),
-          (os.path.join(HERE, "csrc", "access_probe.hip"), os.path.join(HERE, "access_probe"))]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # -ffp-contract=off: the kernels state every fused multiply-add explicitly; the
@@ -38,15 +32,6 @@ def build(verbose: bool = False, extra=()) -> str:
         print("\n".join(lines))
     if r.returncode != 0:
         raise RuntimeError("hipcc failed")
-    # the probes hold no arithmetic of the method: plain -O3, hand-written instruction streams / access patterns
-    for src, out in PROBES:
-        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", src, "-o", out]
-        if verbose:
-            print(" ".join(cmd))
-        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        if r.returncode != 0:
-            print(r.stdout)
-            raise RuntimeError(f"hipcc failed ({os.path.basename(src)})")
     return OUT
 
 

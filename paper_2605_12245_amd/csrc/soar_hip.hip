@@ -5,7 +5,7 @@
 //   absmax   max|W|                                     -> alpha0       (Eq. 1)
 //   stats    per block: Delta0, Q0, a = sum w q, b = sum q^2            (Eq. 1-2)
 //            tensor:    N = sum a Delta0, M = sum b Delta0^2 -> alpha1  (Eq. 5)
-//   search   per block: Delta* = a/(alpha1 b) (Eq. 6), centre = E4M3(Delta*)
+//   search   per block: Delta* = (a/b)/alpha1 (Eq. 6), centre = E4M3(Delta*)
 //            (Appendix D), Q1 = Q_FP4(W/(alpha1 Delta*)), search of the stored
 //            scale over centre-K..centre+K by Eq. 8, pack, error sum
 //
