@@ -45,7 +45,8 @@ typedef enum {
     SOAR_ERR_PARAM = 4,      /* bad soar_params field                               */
     SOAR_ERR_WORKSPACE = 5,  /* workspace missing, misaligned or too small          */
     SOAR_ERR_HIP = 6,        /* a HIP runtime call failed (launch error)            */
-    SOAR_ERR_ALIGN = 7       /* weight/output pointer or leading dimension misaligned */
+    SOAR_ERR_ALIGN = 7,      /* weight/output pointer or leading dimension misaligned */
+    SOAR_ERR_TOO_LARGE = 8   /* soar_quantize_static: more blocks than its built-in workspace holds */
 } soar_status;
 
 typedef enum { SOAR_BF16 = 0, SOAR_FP32 = 1 } soar_dtype;
@@ -169,6 +170,28 @@ soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64
                           uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale,
                           double *d_sse, int32_t *d_status,
                           void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * soar_quantize_static -- soar_quantize for callers that cannot allocate device memory or have
+ * none to hand over as a workspace: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as soar_quantize minus
+ * the workspace: the control words and the 4 bytes per block come from a fixed array inside the
+ * library's device image (SOAR_STATIC_MAX_BLOCKS blocks, about 19 MiB on every GPU the library
+ * runs on, held until the process ends).  The call allocates and frees nothing -- no device
+ * memory, no stream, no event (per-kernel timing is not recorded for it).
+ *   - rows * cols / 16 > SOAR_STATIC_MAX_BLOCKS returns SOAR_ERR_TOO_LARGE before anything is
+ *     enqueued;
+ *   - all calls on one GPU share that array, which keeps the previous call's contents (the
+ *     library clears what must start at zero): calls must be ordered on one stream, or otherwise
+ *     serialised by the caller -- two that overlap on one GPU race;
+ *   - the device current at the call must own hip_stream and the buffers; the first call on a
+ *     device looks the array's address up and must therefore come before any graph capture.
+ */
+#define SOAR_STATIC_MAX_BLOCKS 4194304   /* 2^22 blocks = 2^26 weights, e.g. 8192 x 8192 */
+soar_status soar_quantize_static(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols,
+                                 int64_t ld_elems, const soar_params *params,
+                                 uint8_t *d_codes, uint8_t *d_scales, float *d_global_scale,
+                                 double *d_sse, int32_t *d_status, void *hip_stream);
 
 /* One tensor of a batch: the arguments of soar_quantize that differ per tensor. */
 typedef struct {

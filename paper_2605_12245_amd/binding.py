@@ -15,6 +15,8 @@ from typing import Optional, Sequence
 import torch
 
 SOAR_OK = 0
+SOAR_ERR_TOO_LARGE = 8
+SOAR_STATIC_MAX_BLOCKS = 1 << 22
 SOAR_BF16, SOAR_FP32 = 0, 1
 SOAR_METHOD_RTN, SOAR_METHOD_SOAR, SOAR_METHOD_CJSO_ONLY, SOAR_METHOD_DSS_ONLY = 0, 1, 2, 3
 SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
@@ -26,7 +28,7 @@ SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 
 EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
-    "soar_quantize_batch",
+    "soar_quantize_batch", "soar_quantize_static",
     "soar_dequantize", "soar_recon_error", "soar_dequantize_batch", "soar_recon_error_batch",
     "soar_e2m1_round_f32", "soar_e4m3_project_f32",
     "soar_rcp_midrange_f32",
@@ -115,6 +117,8 @@ def lib():
     L.soar_quantize.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_params), vp, vp, vp, vp, vp,
                                 vp, C.c_size_t, vp]
     L.soar_quantize.restype = i32
+    L.soar_quantize_static.argtypes = [vp, i32, i64, i64, i64, C.POINTER(soar_params), vp, vp, vp, vp, vp, vp]
+    L.soar_quantize_static.restype = i32
     L.soar_quantize_batch.argtypes = [i32, C.POINTER(soar_tensor_desc), C.POINTER(soar_params), vp,
                                       C.c_size_t, vp]
     L.soar_quantize_batch.restype = i32
@@ -225,6 +229,13 @@ def soar_quantize(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales, d
     return int(lib().soar_quantize(d_w, dtype, rows, cols, ld_elems, C.byref(params), d_codes, d_scales,
                                    d_global_scale, d_sse, d_status, d_workspace, workspace_bytes,
                                    hip_stream))
+
+
+def soar_quantize_static(d_w, dtype, rows, cols, ld_elems, params, d_codes, d_scales, d_global_scale,
+                         d_sse, d_status, hip_stream) -> int:
+    """Raw call of the entry point that uses the library's built-in workspace."""
+    return int(lib().soar_quantize_static(d_w, dtype, rows, cols, ld_elems, C.byref(params), d_codes, d_scales,
+                                          d_global_scale, d_sse, d_status, hip_stream))
 
 
 def soar_quantize_batch(descs: Sequence[soar_tensor_desc], params, d_workspace, workspace_bytes,

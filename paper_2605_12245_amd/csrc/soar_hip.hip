@@ -32,6 +32,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "soar.h"
@@ -41,9 +42,35 @@
 #include "soar_mxfp4.hpp"
 #include "soar_stored_form.hpp"
 
+// Workspace of soar_quantize_static: the control slots of one launch and one float per block for a
+// tensor of at most kStaticMaxBlocks blocks.  One copy per GPU, held until the process ends; in host
+// code the name below is only a handle for hipGetSymbolAddress, never an address.
+constexpr int64_t kStaticMaxBlocks = (int64_t)1 << 22;        // 2^26 weights, e.g. 8192 x 8192
+constexpr size_t kStaticScratchBytes = (size_t)kGroupMax * kSlotBytes + (size_t)kStaticMaxBlocks * sizeof(float);
+static_assert(kStaticMaxBlocks == SOAR_STATIC_MAX_BLOCKS, "limit stated in soar.h");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 // ------------------------------------------------------------------ host side
+constexpr int kMaxDevices = 64;
+
+// device address of `scratch` on the current device, looked up once per device; null on failure
+void *static_scratch_address()
+{
+    static std::once_flag once[kMaxDevices];
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::call_once(once[dev], [dev] {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) == hipSuccess) address[dev] = p;
+    });
+    return address[dev];
+}
+
+thread_local bool t_no_event_timing = false;      // set while an entry point that must not create events runs
+
 struct Timing {
     bool enabled = false;
     std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[SOAR_KERNEL_COUNT];
@@ -56,7 +83,7 @@ struct ScopedTimer {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     ScopedTimer(int id_, hipStream_t st_) : id(id_), st(st_)
     {
-        if (!g_timing.enabled) return;
+        if (!g_timing.enabled || t_no_event_timing) return;
         if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e0 = e1 = nullptr; return; }
         (void)hipEventRecord(e0, st);
     }
@@ -588,6 +615,36 @@ soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64
     return run_batch(1, &d, params, d_workspace, workspace_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+soar_status soar_quantize_static(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,
+                                 const soar_params *params, uint8_t *d_codes, uint8_t *d_scales,
+                                 float *d_global_scale, double *d_sse, int32_t *d_status, void *hip_stream)
+{
+    soar_tensor_desc d;
+    d.d_w = d_w;
+    d.dtype = dtype;
+    d.rows = rows;
+    d.cols = cols;
+    d.ld_elems = ld_elems;
+    d.d_codes = d_codes;
+    d.d_scales = d_scales;
+    d.d_global_scale = d_global_scale;
+    d.d_sse = d_sse;
+    d.d_status = d_status;
+    d.d_iters_run = nullptr;
+    d.d_sse_trace = nullptr;
+    d.d_amax_in = nullptr;
+    if (!params) return SOAR_ERR_NULL;
+    soar_status s = validate_tensor(d, params);
+    if (s != SOAR_OK) return s;
+    if (rows * (cols / 16) > kStaticMaxBlocks) return SOAR_ERR_TOO_LARGE;
+    void *ws = static_scratch_address();
+    if (!ws) return SOAR_ERR_HIP;
+    t_no_event_timing = true;
+    s = run_batch(1, &d, params, ws, kStaticScratchBytes, static_cast<hipStream_t>(hip_stream));
+    t_no_event_timing = false;
+    return s;
+}
+
 soar_status soar_quantize_batch(int32_t n, const soar_tensor_desc *descs, const soar_params *params,
                                 void *d_workspace, size_t workspace_bytes, void *hip_stream)
 {
@@ -938,6 +995,7 @@ const char *soar_status_string(soar_status s)
     case SOAR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SOAR_ERR_HIP: return "HIP runtime error";
     case SOAR_ERR_ALIGN: return "misaligned pointer or leading dimension";
+    case SOAR_ERR_TOO_LARGE: return "tensor larger than the built-in workspace of soar_quantize_static";
     }
     return "unknown status";
 }

@@ -18,7 +18,7 @@ int main(void)
     typedef void (*any_fn)(void);
     any_fn fns[] = {
         (any_fn)soar_default_params, (any_fn)soar_paper_params, (any_fn)soar_workspace_bytes,
-        (any_fn)soar_quantize, (any_fn)soar_quantize_batch, (any_fn)soar_batch_workspace_bytes,
+        (any_fn)soar_quantize, (any_fn)soar_quantize_static, (any_fn)soar_quantize_batch, (any_fn)soar_batch_workspace_bytes,
         (any_fn)soar_dequantize, (any_fn)soar_recon_error, (any_fn)soar_dequantize_batch,
         (any_fn)soar_recon_error_batch, (any_fn)soar_e2m1_round_f32, (any_fn)soar_e4m3_project_f32,
         (any_fn)soar_rcp_midrange_f32, (any_fn)soar_mx_default_params, (any_fn)soar_mxfp4_workspace_bytes,

@@ -29,8 +29,8 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_status_strings():
     assert B.soar_version() >= 0x00010000
     L = B.lib()
-    seen = {L.soar_status_string(k).decode() for k in range(8)}
-    assert len(seen) == 8 and "ok" in seen
+    seen = {L.soar_status_string(k).decode() for k in range(9)}
+    assert len(seen) == 9 and "ok" in seen
     assert L.soar_status_string(99).decode() == "unknown status"
 
 
