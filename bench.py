@@ -302,17 +302,17 @@ def main():
             B.quantize_batch(descs, p_one, ws)
         torch.cuda.synchronize()
         names = {B.SOAR_KERNEL_INIT: "init", B.SOAR_KERNEL_ABSMAX: "absmax",
-                 B.SOAR_KERNEL_STATS: "stats", B.SOAR_KERNEL_SEARCH: "search", B.SOAR_KERNEL_SMALL: "small"}
-        # the one-workgroup kernel of a small tensor is the whole path: it is priced on the path's algorithmic bytes
+                 B.SOAR_KERNEL_STATS: "stats", B.SOAR_KERNEL_SEARCH: "search", B.SOAR_KERNEL_RESIDENT: "resident"}
+        # the one-launch kernel of a single tensor is the whole path and reads the weights once
         per_elem = {"absmax": BYTES_ABSMAX, "stats": BYTES_STATS, "search": BYTES_SEARCH, "init": 0.0,
-                    "small": BYTES_ABSMAX + BYTES_SEARCH if rtn_amax else BYTES_ABSMAX + BYTES_STATS + BYTES_SEARCH}
+                    "resident": BYTES_SEARCH}
         for kid, nm in names.items():
             ms, n = B.soar_kernel_timing_read(kid)
             kernels[nm] = {"launches": n, "total_ms": ms, "avg_us": (ms / n * 1e3) if n else None,
                            "ms_per_step": ms / n_prof,
                            "GBps": (per_elem[nm] * E * n_prof / (ms * 1e-3) / 1e9) if ms > 0 and per_elem[nm] else None}
         B.soar_kernel_timing_enable(False)
-        dom = max(("absmax", "stats", "search", "small"), key=lambda k: kernels[k]["total_ms"])
+        dom = max(("absmax", "stats", "search", "resident"), key=lambda k: kernels[k]["total_ms"])
         kernels = {k: v for k, v in kernels.items() if v["launches"]}
         achieved = kernels[dom]["GBps"]
         traffic, traffic_source = traffic_per_launch(args.algorithm, args.workload, args.dtype, "k_" + dom,

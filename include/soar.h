@@ -69,6 +69,12 @@ typedef enum {
     SOAR_SEARCH_FULL = 1     /* evaluate all 2K+1 candidates                        */
 } soar_search_mode;
 
+/* the one-launch kernel for a single tensor, see soar_params.resident */
+typedef enum {
+    SOAR_RESIDENT_AUTO = 0,  /* used when the tensor fits and the grid fits the GPU     */
+    SOAR_RESIDENT_NEVER = 1  /* always the three-pass path                              */
+} soar_resident_mode;
+
 /* which E4M3 codes are candidates for the stored scale Delta^d (Sec. 3.3 (ii)) */
 typedef enum {
     SOAR_DD_WINDOW = 0,      /* centre-K .. centre+K, centre = E4M3(Delta*) (App. D) */
@@ -80,6 +86,10 @@ typedef enum {
 #define SOAR_STATUS_ALLZERO   2   /* every weight is zero                            */
 #define SOAR_STATUS_BAD_AMAX  4   /* supplied maximum not finite or not > 0: outputs
                                      unspecified                                     */
+#define SOAR_STATUS_GAVE_UP   8   /* the one-launch kernel (see soar_params.resident) did not
+                                     get all of its workgroups onto the GPU within
+                                     resident_wait_us and left: outputs unspecified; run the
+                                     call again, or with resident = SOAR_RESIDENT_NEVER    */
 
 typedef struct {
     uint32_t struct_size;    /* sizeof(soar_params), for forward compatibility      */
@@ -105,6 +115,21 @@ typedef struct {
                                 internal stream, forked and joined by events);
                                 1 = everything on the caller's stream             */
     int32_t  dd_mode;        /* soar_dd_mode; dss_radius is ignored for BRACKET     */
+    int32_t  resident;       /* soar_resident_mode: may one tensor handed over alone (single-
+                                step settings, tiles_per_wg 0, at most 4096 blocks per compute
+                                unit: 2^20 blocks = 32 MiB of bf16 on an MI355X) take ONE
+                                launch that keeps the tensor in registers and crosses its two
+                                tensor-wide dependencies (Eq. 1 maximum, Eq. 5 sums) inside
+                                the kernel?  Same bytes as the three-pass path, the weights
+                                are read once.  It needs every workgroup of its grid (at most
+                                one per compute unit) on the GPU at the same time and waits
+                                for that at most resident_wait_us.  A call that arrives on
+                                another stream while an earlier such kernel may still run
+                                takes the three-pass path instead (two of them started at
+                                once could each hold part of the GPU and wait for the rest) */
+    int32_t  resident_wait_us; /* 0 = library default (2 s); > 0: the bound, in microseconds,
+                                after which a workgroup of that kernel stops waiting, sets
+                                SOAR_STATUS_GAVE_UP and leaves (every workgroup then does)   */
 } soar_params;
 
 /* Fills *p with the single-step defaults: SOAR, block 16, T = 1, K = 4, beta = {1},
@@ -404,10 +429,23 @@ soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, voi
 typedef enum {
     SOAR_KERNEL_INIT = 0, SOAR_KERNEL_ABSMAX = 1, SOAR_KERNEL_STATS = 2, SOAR_KERNEL_SEARCH = 3,
     SOAR_KERNEL_DEQUANT = 4, SOAR_KERNEL_RECON = 5, SOAR_KERNEL_ITER_INIT = 6, SOAR_KERNEL_ITER = 7,
-    SOAR_KERNEL_MX = 8, SOAR_KERNEL_SMALL = 9, SOAR_KERNEL_COUNT = 10
+    SOAR_KERNEL_MX = 8, SOAR_KERNEL_RESIDENT = 9, SOAR_KERNEL_COUNT = 10
 } soar_kernel_id;
 void        soar_kernel_timing_enable(int enable);
 soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *launches);
+
+/*
+ * Diagnostics of the Eq. 8 search in SOAR_SEARCH_AUTO (single-step path): the library evaluates the two
+ * candidates that enclose the block's least-squares scale and hands over to the exhaustive loop where it
+ * cannot show that their winner is the exhaustive winner; since a wave walks one block per lane, one such
+ * block makes its whole wave wait for the loop.  soar_search_stats_enable(1) zeroes the counters of the
+ * current device (it synchronises the device) and makes every later launch count; (0) stops the counting.
+ * soar_search_stats_read synchronises the device and returns counts[0] blocks searched, [1] blocks handed
+ * over, [2] wave steps, [3] wave steps with at least one block handed over.  Counting costs atomics: leave
+ * it off when timing.  Not thread-safe.
+ */
+soar_status soar_search_stats_enable(int enable);
+soar_status soar_search_stats_read(int64_t counts[4]);
 
 const char *soar_status_string(soar_status s);
 uint32_t    soar_version(void);

@@ -20,11 +20,12 @@ SOAR_STATIC_MAX_BLOCKS = 1 << 22
 SOAR_BF16, SOAR_FP32 = 0, 1
 SOAR_METHOD_RTN, SOAR_METHOD_SOAR, SOAR_METHOD_CJSO_ONLY, SOAR_METHOD_DSS_ONLY = 0, 1, 2, 3
 SOAR_SEARCH_AUTO, SOAR_SEARCH_FULL = 0, 1
-SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX = 1, 2, 4
+SOAR_STATUS_NONFINITE, SOAR_STATUS_ALLZERO, SOAR_STATUS_BAD_AMAX, SOAR_STATUS_GAVE_UP = 1, 2, 4, 8
+SOAR_RESIDENT_AUTO, SOAR_RESIDENT_NEVER = 0, 1
 SOAR_DD_WINDOW, SOAR_DD_BRACKET = 0, 1
 (SOAR_KERNEL_INIT, SOAR_KERNEL_ABSMAX, SOAR_KERNEL_STATS, SOAR_KERNEL_SEARCH,
  SOAR_KERNEL_DEQUANT, SOAR_KERNEL_RECON, SOAR_KERNEL_ITER_INIT, SOAR_KERNEL_ITER, SOAR_KERNEL_MX,
- SOAR_KERNEL_SMALL, SOAR_KERNEL_COUNT) = range(11)
+ SOAR_KERNEL_RESIDENT, SOAR_KERNEL_COUNT) = range(11)
 
 EXPORTS = (
     "soar_default_params", "soar_paper_params", "soar_workspace_bytes", "soar_batch_workspace_bytes", "soar_quantize",
@@ -35,7 +36,8 @@ EXPORTS = (
     "soar_mx_default_params", "soar_mxfp4_workspace_bytes", "soar_mxfp4_quantize", "soar_mxfp4_dequantize",
     "soar_mxfp4_dequantize_batch",
     "soar_mxfp4_quantize_batch", "soar_mxfp4_batch_workspace_bytes",
-    "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_status_string", "soar_version",
+    "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_search_stats_enable", "soar_search_stats_read",
+    "soar_status_string", "soar_version",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -56,7 +58,7 @@ class soar_params(C.Structure):
         ("iters", C.c_int32), ("dss_radius", C.c_int32), ("n_beta", C.c_int32),
         ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
         ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32), ("streams", C.c_int32),
-        ("dd_mode", C.c_int32),
+        ("dd_mode", C.c_int32), ("resident", C.c_int32), ("resident_wait_us", C.c_int32),
     ]
 
 
@@ -156,6 +158,10 @@ def lib():
     L.soar_kernel_timing_enable.restype = None
     L.soar_kernel_timing_read.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
     L.soar_kernel_timing_read.restype = i32
+    L.soar_search_stats_enable.argtypes = [C.c_int]
+    L.soar_search_stats_enable.restype = i32
+    L.soar_search_stats_read.argtypes = [C.POINTER(i64)]
+    L.soar_search_stats_read.restype = i32
     L.soar_status_string.argtypes = [i32]
     L.soar_status_string.restype = C.c_char_p
     L.soar_version.argtypes = []
@@ -339,6 +345,22 @@ def soar_kernel_timing_read(kernel_id: int):
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_kernel_timing_read")
     return ms.value, n.value
+
+
+def soar_search_stats_enable(enable: bool) -> None:
+    rc = lib().soar_search_stats_enable(1 if enable else 0)
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_search_stats_enable")
+
+
+def soar_search_stats_read() -> dict:
+    """Counters of the certified search since they were enabled: blocks, blocks handed over to the exhaustive
+    loop, wave steps, wave steps with at least one block handed over."""
+    c = (C.c_int64 * 4)()
+    rc = lib().soar_search_stats_read(c)
+    if rc != SOAR_OK:
+        raise SoarError(rc, "soar_search_stats_read")
+    return {"blocks": c[0], "blocks_handed_over": c[1], "wave_steps": c[2], "wave_steps_with_hand_over": c[3]}
 
 
 def soar_version() -> int:

@@ -36,6 +36,7 @@ struct Ctrl {
     uint32_t stopped;        // iterated path: the early stop has fired
     double   N, M;
     double   prev_sse;       // iterated path: error before the iteration now running
+    uint64_t epoch;          // one-launch path: advanced by every launch, part of its token (any start value will do)
 };
 constexpr size_t kCtrlBytes = 256;
 static_assert(sizeof(Ctrl) <= kCtrlBytes, "control block");
@@ -76,6 +77,7 @@ struct Batch {
     uint32_t n;
     int32_t  radius;
     int32_t  full_search;
+    unsigned long long *search_stats;   // null, or four counters (see count_search): diagnostics only
     // iterated path
     int32_t  iter_t;         // iteration this launch carries out
     int32_t  n_beta;

@@ -31,6 +31,8 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <atomic>
+#include <chrono>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -50,10 +52,24 @@ constexpr size_t kStaticScratchBytes = (size_t)kGroupMax * kSlotBytes + (size_t)
 static_assert(kStaticMaxBlocks == SOAR_STATIC_MAX_BLOCKS, "limit stated in soar.h");
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
+// Diagnostic counters of the certified search (count_search), one set per GPU.
+static __device__ unsigned long long search_stats_words[4];
+
 namespace {
 
 // ------------------------------------------------------------------ host side
 constexpr int kMaxDevices = 64;
+
+std::atomic<bool> g_search_stats{false};
+
+// device address of the diagnostic counters on the current device, or null while they are off
+unsigned long long *search_stats_address()
+{
+    if (!g_search_stats.load(std::memory_order_relaxed)) return nullptr;
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(search_stats_words)) != hipSuccess) return nullptr;
+    return static_cast<unsigned long long *>(p);
+}
 
 // device address of `scratch` on the current device, looked up once per device; null on failure
 void *static_scratch_address()
@@ -67,6 +83,98 @@ void *static_scratch_address()
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) == hipSuccess) address[dev] = p;
     });
     return address[dev];
+}
+
+// what the one-launch kernel needs to know of the current device, looked up once per device
+struct DeviceFacts {
+    int compute_units = 0;            // 0: not known, the one-launch kernel is not used
+    int wall_clock_khz = 100000;
+};
+const DeviceFacts &device_facts()
+{
+    static std::once_flag once[kMaxDevices];
+    static DeviceFacts facts[kMaxDevices];
+    static const DeviceFacts none;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return none;
+    std::call_once(once[dev], [dev] {
+        int cu = 0, khz = 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0)
+            facts[dev].compute_units = cu;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+            facts[dev].wall_clock_khz = khz;
+    });
+    return facts[dev];
+}
+
+// a new 64-bit value for every call: half of the token of a one-launch kernel
+uint64_t next_nonce()
+{
+    static std::atomic<uint64_t> state{(uint64_t)std::chrono::steady_clock::now().time_since_epoch().count() * kResOdd};
+    return state.fetch_add(0xD1B54A32D192ED03ull, std::memory_order_relaxed);
+}
+
+// Launch shape of the one-launch kernel for a tensor of nblk blocks on a GPU of `cu` compute units: at most
+// one workgroup per compute unit (and kResMaxWG), so that the whole grid can be on the machine at once.
+struct ResidentPlan { int L, R; uint32_t G; };
+bool resident_plan(int64_t nblk, int cu, ResidentPlan &plan)
+{
+    const int64_t wgs = cu < kResMaxWG ? cu : kResMaxWG;
+    if (wgs < 1) return false;
+    int L = 256, R = 1;
+    if (nblk > 256 * wgs) {
+        L = 1024;
+        while (R <= kResMaxPer && nblk > (int64_t)L * R * wgs) R <<= 1;
+        if (R > kResMaxPer) return false;
+    }
+    plan.L = L;
+    plan.R = R;
+    plan.G = (uint32_t)((nblk + (int64_t)L * R - 1) / ((int64_t)L * R));
+    return true;
+}
+
+// Two one-launch kernels that start at the same time on two streams can each take part of the compute
+// units and then wait for the rest in vain (until the bounded wait gives up).  Calls on one stream are
+// ordered by the stream.  For calls that arrive on a different stream than the one-launch kernel before
+// them, this asks whether that earlier stream has drained; if it has not (or the question cannot be asked:
+// either stream is being captured into a graph), the caller takes the three-pass path for this call.
+// Best effort: replays of captured graphs and other processes on the same GPU are not seen here; the
+// bounded wait and SOAR_STATUS_GAVE_UP cover those.
+bool resident_may_start(hipStream_t st)
+{
+    static std::mutex mu[kMaxDevices];
+    static hipStream_t last[kMaxDevices] = {};
+    static bool have_last[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) return false;
+    if (cap != hipStreamCaptureStatusNone) return true;      // recorded, not started: nothing to track
+    std::lock_guard<std::mutex> lock(mu[dev]);
+    if (have_last[dev] && last[dev] != st) {
+        hipStreamCaptureStatus cap_last = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(last[dev], &cap_last) == hipSuccess) {
+            if (cap_last != hipStreamCaptureStatusNone) return false;     // a query would break that capture
+            const hipError_t q = hipStreamQuery(last[dev]);
+            if (q == hipErrorNotReady) return false;          // may still be running: do not start beside it
+            if (q != hipSuccess) (void)hipGetLastError();
+        } else {
+            (void)hipGetLastError();                          // a stream that no longer exists has nothing in flight
+        }
+    }
+    last[dev] = st;
+    have_last[dev] = true;
+    return true;
+}
+
+template <int DT, int METHOD>
+void launch_resident(const ResidentPlan &plan, const Task &t, const ResidentArgs &a, hipStream_t st)
+{
+    const dim3 grid(plan.G);
+    if (plan.L == 256) hipLaunchKernelGGL((k_resident<DT, METHOD, 256, 1>), grid, dim3(256), 0, st, t, a);
+    else if (plan.R == 1) hipLaunchKernelGGL((k_resident<DT, METHOD, 1024, 1>), grid, dim3(1024), 0, st, t, a);
+    else if (plan.R == 2) hipLaunchKernelGGL((k_resident<DT, METHOD, 1024, 2>), grid, dim3(1024), 0, st, t, a);
+    else hipLaunchKernelGGL((k_resident<DT, METHOD, 1024, 4>), grid, dim3(1024), 0, st, t, a);
 }
 
 thread_local bool t_no_event_timing = false;      // set while an entry point that must not create events runs
@@ -115,6 +223,8 @@ bool valid_params(const soar_params *p)
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
     if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
     if (p->streams < 0 || p->streams > kLanes) return false;
+    if (p->resident != SOAR_RESIDENT_AUTO && p->resident != SOAR_RESIDENT_NEVER) return false;
+    if (p->resident_wait_us < 0) return false;
     return true;
 }
 
@@ -331,9 +441,12 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
     if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
 
-    // one small tensor, default launch shape: the whole path in one workgroup, one launch, no workspace use
-    if (n == 1 && !iterated && !descs[0].d_amax_in && params->tiles_per_wg == 0 &&
-        descs[0].rows * (descs[0].cols / 16) <= (int64_t)kSmallBlocks) {
+    // one tensor, single-step settings, default launch shape: the whole path in one launch that keeps the
+    // tensor in registers, if its grid fits the GPU (see k_resident); only the slot's flag words are used
+    ResidentPlan plan;
+    if (n == 1 && !iterated && !descs[0].d_amax_in && params->tiles_per_wg == 0 && params->resident == SOAR_RESIDENT_AUTO &&
+        resident_plan(descs[0].rows * (descs[0].cols / 16), device_facts().compute_units, plan) &&
+        (plan.G == 1 || resident_may_start(st))) {
         const soar_tensor_desc &d = descs[0];
         Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, 0);
         t.codes = d.d_codes;
@@ -341,15 +454,24 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         t.gscale = d.d_global_scale;
         t.sse = d.d_sse;
         t.status = d.d_status;
-        const int radius = params->dss_radius, full = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        char *slot = static_cast<char *>(d_workspace);
+        t.ctrl = reinterpret_cast<Ctrl *>(slot);
+        t.part = reinterpret_cast<double *>(slot + kZeroedBytes);
+        ResidentArgs a;
+        a.radius = params->dss_radius;
+        a.full_search = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        a.search_stats = search_stats_address();
+        a.nonce = next_nonce();
+        const uint64_t us = params->resident_wait_us > 0 ? (uint64_t)params->resident_wait_us : 2000000ull;
+        a.wait_ticks = us * (uint64_t)device_facts().wall_clock_khz / 1000ull;
         const bool rtn = params->method == SOAR_METHOD_RTN;
-        ScopedTimer tm(SOAR_KERNEL_SMALL, st);
+        ScopedTimer tm(SOAR_KERNEL_RESIDENT, st);
         if (d.dtype == SOAR_BF16) {
-            if (rtn) hipLaunchKernelGGL((k_small<SOAR_BF16, SOAR_METHOD_RTN>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
-            else hipLaunchKernelGGL((k_small<SOAR_BF16, SOAR_METHOD_SOAR>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+            if (rtn) launch_resident<SOAR_BF16, SOAR_METHOD_RTN>(plan, t, a, st);
+            else launch_resident<SOAR_BF16, SOAR_METHOD_SOAR>(plan, t, a, st);
         } else {
-            if (rtn) hipLaunchKernelGGL((k_small<SOAR_FP32, SOAR_METHOD_RTN>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
-            else hipLaunchKernelGGL((k_small<SOAR_FP32, SOAR_METHOD_SOAR>), dim3(1), dim3(kSmallWG), 0, st, t, radius, full);
+            if (rtn) launch_resident<SOAR_FP32, SOAR_METHOD_RTN>(plan, t, a, st);
+            else launch_resident<SOAR_FP32, SOAR_METHOD_SOAR>(plan, t, a, st);
         }
         SOAR_LAUNCH_CHECK();
         return SOAR_OK;
@@ -393,6 +515,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         b.n = (uint32_t)(j - i);
         b.radius = params->dss_radius;
         b.full_search = params->search_mode == SOAR_SEARCH_FULL ? 1 : 0;
+        b.search_stats = search_stats_address();
         b.n_beta = params->n_beta;
         b.dd_mode = params->dd_mode;
         b.beta_lo = params->beta_lo;
@@ -564,6 +687,8 @@ void soar_default_params(soar_params *p)
     p->tiles_per_wg = 0;
     p->streams = 0;
     p->dd_mode = SOAR_DD_WINDOW;
+    p->resident = SOAR_RESIDENT_AUTO;
+    p->resident_wait_us = 0;
 }
 
 void soar_paper_params(soar_params *p)
@@ -981,6 +1106,30 @@ soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *la
     }
     *total_ms = sum;
     *launches = (int64_t)g_timing.ev[kernel_id].size();
+    return SOAR_OK;
+}
+
+soar_status soar_search_stats_enable(int enable)
+{
+    g_search_stats.store(false);
+    if (enable) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(search_stats_words)) != hipSuccess) return SOAR_ERR_HIP;
+        if (hipDeviceSynchronize() != hipSuccess || hipMemset(p, 0, sizeof(unsigned long long) * 4) != hipSuccess ||
+            hipDeviceSynchronize() != hipSuccess)
+            return SOAR_ERR_HIP;
+        g_search_stats.store(true);
+    }
+    return SOAR_OK;
+}
+
+soar_status soar_search_stats_read(int64_t counts[4])
+{
+    if (!counts) return SOAR_ERR_NULL;
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(search_stats_words)) != hipSuccess) return SOAR_ERR_HIP;
+    if (hipDeviceSynchronize() != hipSuccess) return SOAR_ERR_HIP;
+    if (hipMemcpy(counts, p, sizeof(int64_t) * 4, hipMemcpyDeviceToHost) != hipSuccess) return SOAR_ERR_HIP;
     return SOAR_OK;
 }
 

@@ -236,6 +236,8 @@ __device__ __forceinline__ int search_rank(int code, int centre)
 //        worst-case rounding error of the binary32 evaluation (18 ulp relative,
 //        all terms being non-negative), so no unevaluated candidate can compute
 //        to a value as small as the winner's.
+// Where only one side of the bracket fails (i) -- s* within the margin of a candidate -- the next
+// candidate on that side is evaluated as well and (i) is asked of the three.
 // Returns false when a condition cannot be shown; the caller then runs the
 // exhaustive search, so the result never depends on this shortcut.
 __device__ __forceinline__ bool search_certified(const float w[16], const float q[16], float alpha1,
@@ -265,9 +267,40 @@ __device__ __forceinline__ bool search_certified(const float w[16], const float 
     best_err = b_wins ? fb : fa;
     const bool left_ok = (ka == wmin) || (sa * (1.0f + 0x1p-17f) <= sstar);
     const bool right_ok = (kb == wmax) || (sb * (1.0f - 0x1p-17f) >= sstar);
+    bool enclosed = left_ok && right_ok;
+    if (left_ok != right_ok) {
+        // s* sits within the margin of one of the two candidates (about two blocks in ten thousand), so that
+        // side of the bracket is in doubt: the next candidate on that side, a whole E4M3 step further out,
+        // settles it -- the three enclose s* if it lies clear of s* in its turn.  Its rank in the search
+        // order decides ties as in the exhaustive loop.
+        const int ke = left_ok ? kb + 1 : ka - 1;            // inside the window: the side in doubt is not at its edge
+        const float se = alpha1 * e4m3_value((uint32_t)ke);
+        const float fe = block_error(w, q, se);
+        enclosed = left_ok ? (ke == wmax) || (se * (1.0f - 0x1p-17f) >= sstar)
+                           : (ke == wmin) || (se * (1.0f + 0x1p-17f) <= sstar);
+        if (fe < best_err || (fe == best_err && search_rank(ke, centre) < search_rank(best, centre))) {
+            best = ke;
+            best_err = fe;
+        }
+    }
     const bool margin_ok = best_err < 512.0f * (C * (sa * sa));
     const bool range_ok = (B > 0x1p-100f) && (best_err > 0x1p-100f) && (C > 0.0f);
-    return left_ok && right_ok && margin_ok && range_ok;
+    return enclosed && margin_ok && range_ok;
+}
+
+// Diagnostics (off unless the host asks): how often the certified search had to hand over to the
+// exhaustive one.  stats[0] blocks searched, [1] blocks that fell back, [2] wave steps (one block per lane),
+// [3] wave steps in which at least one lane fell back (the whole wave then waits for the exhaustive loop).
+__device__ __forceinline__ void count_search(unsigned long long *stats, bool certified)
+{
+    const unsigned long long active = __builtin_amdgcn_ballot_w64(true);
+    const unsigned long long fell = __builtin_amdgcn_ballot_w64(!certified);
+    if ((threadIdx.x & 63u) == (uint32_t)__builtin_ctzll(active)) {
+        atomicAdd(stats + 0, (unsigned long long)__builtin_popcountll(active));
+        atomicAdd(stats + 1, (unsigned long long)__builtin_popcountll(fell));
+        atomicAdd(stats + 2, 1ull);
+        atomicAdd(stats + 3, fell != 0ull ? 1ull : 0ull);
+    }
 }
 
 // Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
@@ -346,7 +379,10 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
             int best;
             float best_err;
             bool done = false;
-            if (!full_search) done = search_certified(w, q, alpha1, inv_alpha1, centre, radius, best, best_err);
+            if (!full_search) {
+                done = search_certified(w, q, alpha1, inv_alpha1, centre, radius, best, best_err);
+                if (batch.search_stats) count_search(batch.search_stats, done);
+            }
             if (!done) search_full(w, q, alpha1, centre, radius, best, best_err);
             out_code = (uint32_t)best;
             out_err = best_err;
@@ -383,50 +419,344 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     reset_counters(counters, &t.ctrl->top[2]);
 }
 
-// The whole single-step path for one small tensor in one workgroup: a tensor of at most
-// kSmallBlocks blocks is latency-bound on the four dependent launches of the path above; here the
-// 1024 lanes keep their (up to four) blocks in registers, and the two tensor-wide results cross
-// the workgroup through LDS and a barrier.  Same arithmetic, same trees: lane `tid` owns the
-// blocks tid, tid + 1024, ...; a wave's DPP tree sums 64 consecutive blocks, and the 4 x 16 wave
-// sums, laid out in block order over the lanes of wave 0, go through the same DPP tree again --
-// together the adjacent-pair tree over the flat block index, zero-padded.  No workspace is used.
-constexpr int kSmallWG = 1024;
-constexpr int kSmallPer = 4;                               // blocks per lane, at most
-constexpr uint32_t kSmallBlocks = kSmallWG * kSmallPer;
-template <int DT, int METHOD>
-__global__ __launch_bounds__(kSmallWG) void k_small(const Task t, const int radius, const int full_search)
+// ------------------------------------------------------------------ one launch, the tensor resident on chip
+// A tensor handed over alone pays, on the three-pass path, four dependent launches whose ramp and tail
+// dominate below a few hundred MiB, and reads its weights three times.  k_resident does the whole
+// single-step path in ONE launch of at most one workgroup per compute unit: every lane loads its (up to
+// kResMaxPer) blocks once and keeps them in registers as loaded; the two tensor-wide results (the Eq. 1
+// maximum, the Eq. 5 sums) cross the grid through words in the workspace; the search then runs from the
+// registers.  The weights are read once (2 + 9/16 bytes per bf16 weight instead of 6 + 9/16).
+//
+// Workgroup g owns the L * R consecutive blocks from g * L * R on (an aligned power of two, so its partial
+// sums are nodes of the adjacent-pair tree) and a wave 64 R consecutive ones, in "packets" of up to 128
+// bytes of weights per lane: a lane owns ADJACENT blocks (4 bf16 or 2 fp32 blocks per packet; with four
+// fp32 blocks per lane a wave's range is two packets).  So the first levels of the tree are additions in
+// registers, one DPP wave tree covers a packet of the whole wave, the L/64 wave sums, in block order, go
+// through the wave tree once more, and a lane's scale bytes and code bytes leave in one or two stores.
+// Packed rows are read through the coalescing wave exchange (load_wave_pieces).  Across workgroups the tree continues over groups of 64 consecutive workgroups (one wave
+// tree, a workgroup per lane) and then over the at most 4 groups.  Same arithmetic, same trees as the
+// three-pass path: identical bytes.
+//
+// Crossing the grid.  All workgroups of the launch must be on the machine at the same time (the host
+// launches at most one per compute unit and takes the three-pass path otherwise).  A trip through memory
+// from one workgroup to another takes about 1.4 us on this part, and 256 workgroups that each read all
+// 256 results queue for several microseconds more, so:
+//  - there is no counter and no separate "ready" flag, hence no word that has to be cleared beforehand and
+//    no second trip for the value: every word a workgroup publishes (an agent-scope atomic store) carries
+//    the launch's TOKEN beside its payload, and a reader accepts a word only with that token.  A binary64
+//    sum travels as three words of 22 payload bits and 42 token bits; the first crossing's word holds the
+//    bf16 / fp32 maximum in 15 / 31 bits beside 49 / 33 token bits.  The token is `nonce ^ epoch * odd`:
+//    the nonce comes from the host (new for every call), the epoch from the workspace, advanced by the
+//    launch itself once every workgroup has read it (workgroup 0, after the first crossing), so that a
+//    replayed HIP graph -- same kernel arguments -- still sees a new token every time.  Memory the library
+//    never wrote matches a token field with probability 2^-42 (2^-33) per word;
+//  - up to 64 workgroups read each other's words directly (one trip); above that the first workgroup of
+//    every group of 64 gathers its group and publishes the group's result, and everybody gathers the at
+//    most 4 group results (two trips, little traffic); the error sum, which only workgroup 0 needs, is
+//    gathered by workgroup 0 alone in one trip.
+// Every wait is BOUNDED: a workgroup whose time is up publishes the complemented token in its words (so
+// that the others leave at once instead of waiting out the limit), sets SOAR_STATUS_GAVE_UP and returns;
+// every wave of the grid then reaches its end.
+constexpr int kResMaxWG = 256;            // workgroups of one launch, at most
+constexpr int kResMaxPer = 4;             // blocks per lane, at most
+constexpr int kResGroup = 64;             // workgroups per group: a wave gathers one with a workgroup per lane
+constexpr int kResGroups = kResMaxWG / kResGroup;
+constexpr uint64_t kResOdd = 0x9E3779B97F4A7C15ull;
+constexpr int kResSumBits = 22;           // payload bits of a word that carries a third of a binary64 value
+// Places inside Task::part, in 8-byte words.  First level: per kind of word kResMaxWG entries (one per
+// workgroup).  Second level: kResGroups entries (one per group) per kind, in kResCopies copies
+// kResCopyStride words apart: every workgroup polls the second level, and a few lines polled by 250
+// workgroups at once queue at their memory channel (the publisher's stores behind them); a reader polls
+// the copy of its own number modulo kResCopies.
+constexpr int kResCopies = 8;
+constexpr uint32_t kResCopyStride = 544;                                          // 17 * 256 bytes
+constexpr uint32_t kResMax1 = 0;                                                  // 1 kind: token | maximum
+constexpr uint32_t kResNM1 = 512;                                                 // 6 kinds: N and M in thirds
+constexpr uint32_t kResErr1 = 2304;                                               // 3 kinds: the error sum in thirds
+constexpr uint32_t kResMax2 = 3072, kResNM2 = kResMax2 + kResCopies * kResCopyStride;
+static_assert(kResMax1 + kResMaxWG <= kResNM1 && kResNM1 + 6 * kResMaxWG <= kResErr1 && kResErr1 + 3 * kResMaxWG <= kResMax2 &&
+              6 * kResGroups <= kResCopyStride && kResNM2 + kResCopies * kResCopyStride <= 3 * kMaxPartials,
+              "layout of the crossing words");
+constexpr uint32_t kResDirect = 16;       // up to this many workgroups read each other's words directly
+
+struct ResidentArgs {
+    int32_t  radius, full_search;
+    uint64_t nonce;                       // new for every call
+    uint64_t wait_ticks;                  // bound of the waits of a workgroup together, in ticks of the wall clock
+    unsigned long long *search_stats;     // null, or the diagnostic counters of count_search
+};
+
+// what wave 0 of a workgroup needs for its crossings
+struct ResidentGrid {
+    uint32_t g, G;
+    uint64_t tok, t0, ticks;
+    uint64_t *words;                      // Task::part
+};
+
+// The bound of a wait: the wall clock (100 MHz on this part), and -- should that clock ever stand still -- a
+// number of polling rounds that takes several times as long (a round is at least one trip to memory).
+__device__ __forceinline__ bool resident_time_is_up(const ResidentGrid &r, uint64_t round)
 {
-    constexpr int kWaves = kSmallWG / 64;
+    return (uint64_t)wall_clock64() - r.t0 > r.ticks || round > 1024ull + r.ticks / 8ull;
+}
+
+// one lane: NW kinds of words for entry e; kind w of entry e sits at dst[w * stride + e]
+template <int NW, int PBITS>
+__device__ __forceinline__ void resident_publish(uint64_t *dst, uint32_t stride, uint32_t e, uint64_t tok, const uint64_t pay[NW])
+{
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+        __hip_atomic_store(dst + w * stride + e, (tok << PBITS) | pay[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// wave 0, all lanes: a group's result into every copy of the second level (lane c writes copy c)
+template <int NW, int PBITS>
+__device__ __forceinline__ void resident_publish_copies(uint64_t *dst, uint32_t grp, uint64_t tok, const uint64_t pay[NW])
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    if (lane < (uint32_t)kResCopies) resident_publish<NW, PBITS>(dst + lane * kResCopyStride, kResGroups, grp, tok, pay);
+}
+
+// Wave 0, all lanes: wait until entries first .. first + count - 1 (count <= 64 * K) of all NW kinds carry the
+// token; lane l then holds the payloads of entries first + l + 64 k in pay[k][.] (zeros from `count` on).
+// False when somebody has given up (a word with the complemented token) or the time is up.
+template <int NW, int PBITS, int K>
+__device__ __forceinline__ bool resident_gather(const ResidentGrid &r, const uint64_t *src, uint32_t stride, uint32_t first,
+                                                uint32_t count, uint64_t pay[K][NW])
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t want = (r.tok << PBITS) >> PBITS, gone_field = (~r.tok << PBITS) >> PBITS;
+    for (uint64_t round = 0;; ++round) {
+        bool pending = false, gone = false;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t e = lane + 64u * (uint32_t)k;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) pay[k][w] = 0ull;
+            if (e < count) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const uint64_t v = __hip_atomic_load(src + w * stride + first + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint64_t field = v >> PBITS;
+                    gone = gone || field == gone_field;
+                    pending = pending || field != want;
+                    pay[k][w] = v & ((1ull << PBITS) - 1ull);
+                }
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(gone) != 0ull) return false;
+        if (__builtin_amdgcn_ballot_w64(pending) == 0ull) return true;
+        if (resident_time_is_up(r, round)) return false;
+    }
+}
+
+// Wave 0, all lanes: the maximum of `value` over the grid (uniform on return).
+template <int PBITS>
+__device__ __forceinline__ bool resident_cross_max(const ResidentGrid &r, uint32_t &value)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t grp = r.g / kResGroup, groups = (r.G + kResGroup - 1) / kResGroup;
+    uint64_t pay[1][1] = {{value}};
+    if (lane == 0) resident_publish<1, PBITS>(r.words + kResMax1, kResMaxWG, r.g, r.tok, pay[0]);
+    if (r.G > kResDirect) {
+        if (r.g % kResGroup == 0u) {
+            if (!resident_gather<1, PBITS, 1>(r, r.words + kResMax1, kResMaxWG, grp * kResGroup,
+                                              min((uint32_t)kResGroup, r.G - grp * kResGroup), pay)) return false;
+            pay[0][0] = wave_max_u32((uint32_t)pay[0][0]);
+            resident_publish_copies<1, PBITS>(r.words + kResMax2, grp, r.tok, pay[0]);
+        }
+        if (!resident_gather<1, PBITS, 1>(r, r.words + kResMax2 + (r.g % kResCopies) * kResCopyStride, kResGroups, 0u, groups, pay))
+            return false;
+    } else if (!resident_gather<1, PBITS, 1>(r, r.words + kResMax1, kResMaxWG, 0u, r.G, pay)) {
+        return false;
+    }
+    value = wave_max_u32((uint32_t)pay[0][0]);
+    return true;
+}
+
+__device__ __forceinline__ void resident_split(double v, uint64_t pay[3])
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    pay[0] = b & ((1ull << kResSumBits) - 1ull);
+    pay[1] = (b >> kResSumBits) & ((1ull << kResSumBits) - 1ull);
+    pay[2] = b >> (2 * kResSumBits);
+}
+
+__device__ __forceinline__ double resident_join(const uint64_t pay[3])
+{
+    return __longlong_as_double((long long)(pay[0] | pay[1] << kResSumBits | pay[2] << (2 * kResSumBits)));
+}
+
+// Wave 0, all lanes, every workgroup: the adjacent-pair tree sums of NV binary64 values (one set per
+// workgroup, in workgroup order, zero-padded) over the grid; uniform on return.
+template <int NV>
+__device__ __forceinline__ bool resident_cross_sums(const ResidentGrid &r, uint32_t at1, uint32_t at2, double v[NV])
+{
+    constexpr int NW = 3 * NV, P = kResSumBits;
+    static_assert(NW * kResGroups <= (int)kResCopyStride, "a copy holds every kind");
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t grp = r.g / kResGroup, groups = (r.G + kResGroup - 1) / kResGroup;
+    uint64_t pay[1][NW];
+    auto split = [&]() {
+#pragma unroll
+        for (int n = 0; n < NV; ++n) resident_split(v[n], &pay[0][3 * n]);
+    };
+    auto tree = [&]() {                   // lane e holds entry e
+#pragma unroll
+        for (int n = 0; n < NV; ++n) v[n] = wave_pair_tree(resident_join(&pay[0][3 * n]));
+    };
+    split();
+    if (lane == 0) resident_publish<NW, P>(r.words + at1, kResMaxWG, r.g, r.tok, pay[0]);
+    if (r.G > kResDirect) {
+        if (r.g % kResGroup == 0u) {
+            if (!resident_gather<NW, P, 1>(r, r.words + at1, kResMaxWG, grp * kResGroup,
+                                           min((uint32_t)kResGroup, r.G - grp * kResGroup), pay)) return false;
+            tree();
+            split();
+            resident_publish_copies<NW, P>(r.words + at2, grp, r.tok, pay[0]);
+        }
+        if (!resident_gather<NW, P, 1>(r, r.words + at2 + (r.g % kResCopies) * kResCopyStride, kResGroups, 0u, groups, pay))
+            return false;
+    } else if (!resident_gather<NW, P, 1>(r, r.words + at1, kResMaxWG, 0u, r.G, pay)) {
+        return false;
+    }
+    tree();
+    return true;
+}
+
+// Wave 0, all lanes: the same sum of ONE value, wanted by workgroup 0 only, which gathers all workgroups in
+// one trip (lane l holds workgroups l, l + 64, ...: the tree of a group is a wave tree, the groups follow);
+// the other workgroups return as soon as they have published.
+__device__ __forceinline__ bool resident_collect_sum(const ResidentGrid &r, uint32_t at1, double &v)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    uint64_t pay[kResGroups][3];
+    resident_split(v, pay[0]);
+    if (lane == 0) resident_publish<3, kResSumBits>(r.words + at1, kResMaxWG, r.g, r.tok, pay[0]);
+    if (r.g != 0u) return true;
+    if (!resident_gather<3, kResSumBits, kResGroups>(r, r.words + at1, kResMaxWG, 0u, r.G, pay)) return false;
+    double s[kResGroups];
+#pragma unroll
+    for (int k = 0; k < kResGroups; ++k) s[k] = wave_pair_tree(resident_join(pay[k]));
+    static_assert(kResGroups == 4, "the tree over the groups is written out");
+    v = (s[0] + s[1]) + (s[2] + s[3]);
+    return true;
+}
+
+template <int DT, int METHOD, int L, int R>
+__global__ __launch_bounds__(L) void k_resident(const Task t, const ResidentArgs args)
+{
+    static_assert(L == 256 || L == 1024, "workgroup of 4 or 16 waves");
+    static_assert(R == 1 || R == 2 || R == 4, "blocks per lane");
+    constexpr int kWaves = L / 64;
+    constexpr int kParts = kWaves;                           // wave sums of a workgroup, in block order
     constexpr int kP = pieces_per_block<DT, 16>();
+    constexpr int kX = R * kP <= 8 ? R : 8 / kP;             // adjacent blocks of a lane in one packet (<= 128 bytes)
+    constexpr int kPackets = R / kX;                         // 1 or 2
+    constexpr int kXP = kX * kP;                             // 16-byte pieces of a lane per packet: 2, 4 or 8
+    static_assert(kPackets == 1 || kPackets == 2, "packets of a wave");
+    __shared__ u32x4 s_x[kWaves * 64 * kXP];                 // load_wave_pieces: one region per wave
+    // first crossing: bf16 maxima have 15 significant bits (sign cleared, low half zero), fp32 ones 31
+    constexpr int kMaxBits = DT == SOAR_BF16 ? 15 : 31;
     __shared__ uint32_t s_max[kWaves];
-    __shared__ double s_part[3][kSmallPer * kWaves];
+    __shared__ double s_part[3][kParts];
     __shared__ float s_alpha1;
+    __shared__ uint32_t s_amax, s_gone;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t wave_first = (blockIdx.x * (uint32_t)L + wave * 64u) * (uint32_t)R;   // first block of this wave
+    // block k (0 .. R-1) of this lane: packet k / kX of the wave, there the lane's kX adjacent blocks
+    auto blk = [&](int k) -> uint32_t {
+        return wave_first + (uint32_t)(k / kX) * (64u * kX) + lane * (uint32_t)kX + (uint32_t)(k % kX);
+    };
+    uint64_t *epoch_p = &t.ctrl->epoch;
+
+    ResidentGrid grid;
+    grid.g = blockIdx.x;
+    grid.G = gridDim.x;
+    grid.tok = 0;
+    grid.t0 = 0;
+    grid.ticks = args.wait_ticks;
+    grid.words = reinterpret_cast<uint64_t *>(t.part);
+    uint64_t epoch = 0;
+    if (grid.G > 1u) {
+        epoch = __hip_atomic_load(epoch_p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        grid.tok = args.nonce ^ (epoch * kResOdd);
+        grid.t0 = (uint64_t)wall_clock64();
+    }
+    // one lane: leave the launch and tell the others -- whoever gathers this workgroup's words, now or at a
+    // later crossing, finds the complemented token in the first of them
+    auto give_up = [&]() {
+        const uint64_t gone = ~grid.tok << kResSumBits, gone_max = ~grid.tok << kMaxBits;
+        __hip_atomic_store(grid.words + kResMax1 + grid.g, gone_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(grid.words + kResNM1 + grid.g, gone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(grid.words + kResErr1 + grid.g, gone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (grid.g % kResGroup == 0u) {
+            for (int c = 0; c < kResCopies; ++c) {
+                __hip_atomic_store(grid.words + kResMax2 + c * kResCopyStride + grid.g / kResGroup, gone_max, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(grid.words + kResNM2 + c * kResCopyStride + grid.g / kResGroup, gone, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // any change of the epoch will do for the next launch
+        __hip_atomic_fetch_add(epoch_p, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t.status) *t.status = SOAR_STATUS_GAVE_UP;
+    };
 
     // ---- the blocks of this lane, as loaded; Eq. 1 maximum
-    u32x4 raw[kSmallPer][kP];
+    u32x4 raw[R][kP];
     uint32_t m = 0;
+    if (t.contiguous) {
+        // packed rows: the wave reads each packet's range in coalesced 16-byte pieces (all of its lanes take part)
 #pragma unroll
-    for (int k = 0; k < kSmallPer; ++k) {
-        const uint32_t i = (uint32_t)k * kSmallWG + tid;
+        for (int pk = 0; pk < kPackets; ++pk) {
+            const uint32_t first = wave_first + (uint32_t)pk * (64u * kX);
+            const uint32_t have = first < t.nblk ? min(64u * kX, t.nblk - first) * (uint32_t)kP : 0u;
+            u32x4 v[kXP];
+            load_wave_pieces<kXP, true>(static_cast<const u32x4 *>(t.w) + (size_t)first * kP, have, s_x + wave * (64 * kXP), v);
 #pragma unroll
-        for (int p = 0; p < kP; ++p) raw[k][p] = u32x4{0u, 0u, 0u, 0u};
-        if (i < t.nblk) {
-            const char *src = static_cast<const char *>(t.w) + block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
+            for (int q = 0; q < kXP; ++q) raw[pk * kX + q / kP][q % kP] = v[q];
+        }
+    } else {
 #pragma unroll
-            for (int p = 0; p < kP; ++p) {
-                raw[k][p] = load16<false>(src + 16 * p);
-                m = absmax_accumulate<DT>(m, make_uint4(raw[k][p].x, raw[k][p].y, raw[k][p].z, raw[k][p].w));
+        for (int k = 0; k < R; ++k) {
+            const uint32_t i = blk(k);
+#pragma unroll
+            for (int p = 0; p < kP; ++p) raw[k][p] = u32x4{0u, 0u, 0u, 0u};
+            if (i < t.nblk) {
+                const char *src = static_cast<const char *>(t.w) + block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
+#pragma unroll
+                for (int p = 0; p < kP; ++p) raw[k][p] = load16<false>(src + 16 * p);
             }
         }
     }
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+#pragma unroll
+        for (int p = 0; p < kP; ++p)
+            m = absmax_accumulate<DT>(m, make_uint4(raw[k][p].x, raw[k][p].y, raw[k][p].z, raw[k][p].w));
     if constexpr (DT == SOAR_BF16) m = max(m & 0xFFFFu, m >> 16) << 16;
     m = wave_max_u32(m);
     if (lane == 0) s_max[wave] = m;
     __syncthreads();
-    uint32_t amax_bits = 0;
-#pragma unroll
-    for (int w2 = 0; w2 < kWaves; ++w2) amax_bits = max(amax_bits, s_max[w2]);
+    if (wave == 0) {
+        uint32_t amax = wave_max_u32(lane < (uint32_t)kWaves ? s_max[lane] : 0u);
+        bool ok = true;
+        if (grid.G > 1u) {
+            uint32_t value = DT == SOAR_BF16 ? amax >> 16 : amax;
+            ok = resident_cross_max<kMaxBits>(grid, value);
+            amax = DT == SOAR_BF16 ? value << 16 : value;
+            if (lane == 0) {
+                if (!ok) give_up();
+                else if (grid.g == 0u)     // every workgroup has read the epoch by now: the next launch gets a new token
+                    __hip_atomic_store(epoch_p, epoch + 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if (lane == 0) { s_amax = amax; s_gone = ok ? 0u : 1u; }
+    }
+    __syncthreads();
+    if (s_gone) return;
+    const uint32_t amax_bits = s_amax;
     const bool allzero = amax_bits == 0u;
     const bool degenerate = allzero || amax_bits >= 0x7F800000u;
     const float alpha0 = f_of(amax_bits) / 2688.0f;
@@ -451,99 +781,164 @@ __global__ __launch_bounds__(kSmallWG) void k_small(const Task t, const int radi
             }
         }
     };
-    // sum of one binary64 term per block over the tensor: every lane of the workgroup calls it
-    auto tensor_sum = [&](int which, const double term[kSmallPer]) -> double {
+    // one binary64 term per block of the lane: the adjacent-pair tree over the lane's blocks of a packet in
+    // registers, over the packet with the wave tree, over the packets; the wave sum goes to its place in block order
+    auto wave_sum_to_lds = [&](int which, const double term[R]) {
+        double v[kPackets];
 #pragma unroll
-        for (int k = 0; k < kSmallPer; ++k) {
-            const double v = wave_pair_tree(term[k]);
-            if (lane == 0) s_part[which][k * kWaves + wave] = v;
+        for (int pk = 0; pk < kPackets; ++pk) {
+            const double *x = term + pk * kX;
+            double f;
+            if constexpr (kX == 1) f = x[0];
+            else if constexpr (kX == 2) f = x[0] + x[1];
+            else f = (x[0] + x[1]) + (x[2] + x[3]);
+            v[pk] = wave_pair_tree(f);
         }
-        __syncthreads();
-        return wave_pair_tree(s_part[which][lane]);        // 4 x 16 wave sums in block order
+        if (lane == 0) s_part[which][wave] = kPackets == 1 ? v[0] : v[0] + v[kPackets - 1];
+    };
+    // wave 0, after a barrier: the sum over the workgroup's blocks
+    auto workgroup_sum = [&](int which) -> double {
+        return wave_pair_tree(lane < (uint32_t)kParts ? s_part[which][lane] : 0.0);
     };
 
     // ---- Eq. 1-2 state and Eq. 5
     float alpha1 = alpha0;
-    float rho[kSmallPer];
+    float rho[R];
 #pragma unroll
-    for (int k = 0; k < kSmallPer; ++k) rho[k] = 0.0f;
+    for (int k = 0; k < R; ++k) rho[k] = 0.0f;
     if constexpr (METHOD == SOAR_METHOD_SOAR) {
-        double tN[kSmallPer], tM[kSmallPer];
+        if (!degenerate) {                                   // uniform over the grid
+            double tN[R], tM[R];
 #pragma unroll
-        for (int k = 0; k < kSmallPer; ++k) {
-            tN[k] = tM[k] = 0.0;
-            const uint32_t i = (uint32_t)k * kSmallWG + tid;
-            if (i < t.nblk && !degenerate) {
-                float w[16], q[16];
-                uint32_t nib[2], c0;
-                float delta0, a, b;
-                widen(k, w);
-                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
-                block_sums(w, q, a, b);
-                tN[k] = (double)a * (double)delta0;
-                tM[k] = ((double)b * (double)delta0) * (double)delta0;
-                rho[k] = (b == 0.0f) ? -delta0 : a / b;      // first half of Eq. 6
+            for (int k = 0; k < R; ++k) {
+                tN[k] = tM[k] = 0.0;
+                if (blk(k) < t.nblk) {
+                    float w[16], q[16];
+                    uint32_t nib[2], c0;
+                    float delta0, a, b;
+                    widen(k, w);
+                    block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                    block_sums(w, q, a, b);
+                    tN[k] = (double)a * (double)delta0;
+                    tM[k] = ((double)b * (double)delta0) * (double)delta0;
+                    rho[k] = (b == 0.0f) ? -delta0 : a / b;      // first half of Eq. 6
+                }
             }
+            wave_sum_to_lds(0, tN);
+            wave_sum_to_lds(1, tM);
+            __syncthreads();
+            if (wave == 0) {
+                double NM[2] = {workgroup_sum(0), workgroup_sum(1)};
+                bool ok = true;
+                if (grid.G > 1u) {
+                    ok = resident_cross_sums<2>(grid, kResNM1, kResNM2, NM);
+                    if (!ok && lane == 0) give_up();
+                }
+                if (lane == 0) {
+                    s_alpha1 = (NM[1] > 0.0) ? (float)(NM[0] / NM[1]) : alpha0;
+                    s_gone = ok ? 0u : 1u;
+                }
+            }
+            __syncthreads();
+            if (s_gone) return;
+            alpha1 = s_alpha1;
+        } else if (allzero) {
+            alpha1 = 1.0f;
         }
-        const double N = tensor_sum(0, tN);
-        const double M = tensor_sum(1, tM);
-        if (tid == 0) {
-            float a1 = (M > 0.0) ? (float)(N / M) : alpha0;
-            if (allzero) a1 = 1.0f;
-            s_alpha1 = a1;
-            *t.gscale = a1;
-        }
-        __syncthreads();
-        alpha1 = s_alpha1;
+        if (blockIdx.x == 0u && tid == 0) *t.gscale = alpha1;
     }
     const float inv_alpha1 = __builtin_amdgcn_rcpf(alpha1);
+    const bool full_search = args.full_search != 0;
 
-    // ---- Eq. 6, new assignment, Eq. 8 search, packing (k_search, per block)
-    double terr[kSmallPer];
+    // ---- Eq. 6, new assignment, Eq. 8 search (k_search, per block); the lane's bytes leave together
+    double terr[R];
+    uint32_t nibs[R][2], codes4 = 0u;
 #pragma unroll
-    for (int k = 0; k < kSmallPer; ++k) {
+    for (int k = 0; k < R; ++k) {
         terr[k] = 0.0;
-        const uint32_t i = (uint32_t)k * kSmallWG + tid;
-        if (i < t.nblk) {
+        nibs[k][0] = nibs[k][1] = 0u;
+        if (blk(k) < t.nblk) {
             float w[16], q[16];
-            uint32_t nib[2], out_code;
+            uint32_t out_code;
             float out_err;
             widen(k, w);
             if (allzero) {
                 float x[16];
 #pragma unroll
                 for (int j = 0; j < 16; ++j) x[j] = w[j];
-                nib[0] = fp4x8(x);
-                nib[1] = fp4x8(x + 8);
+                nibs[k][0] = fp4x8(x);
+                nibs[k][1] = fp4x8(x + 8);
                 out_code = kE4M3Min;
                 out_err = 0.0f;
             } else if constexpr (METHOD == SOAR_METHOD_RTN) {
                 uint32_t c0;
                 float delta0;
-                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                block_init(w, alpha0, alpha0_m, c0, delta0, nibs[k], q);
                 out_code = c0;
                 out_err = block_error(w, q, alpha0 * delta0);
             } else {
                 const float delta_star = (rho[k] < 0.0f) ? -rho[k] : rho[k] / alpha1;
                 const int centre = (int)e4m3_project(delta_star);
-                assign_codes(w, alpha1 * delta_star, nib, q);
+                assign_codes(w, alpha1 * delta_star, nibs[k], q);
                 int best;
                 float best_err;
                 bool done = false;
-                if (!full_search) done = search_certified(w, q, alpha1, inv_alpha1, centre, radius, best, best_err);
-                if (!done) search_full(w, q, alpha1, centre, radius, best, best_err);
+                if (!full_search) {
+                    done = search_certified(w, q, alpha1, inv_alpha1, centre, args.radius, best, best_err);
+                    if (args.search_stats) count_search(args.search_stats, done);
+                }
+                if (!done) search_full(w, q, alpha1, centre, args.radius, best, best_err);
                 out_code = (uint32_t)best;
                 out_err = best_err;
             }
-            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-            u32x2 packed = {nib[0], nib[1]};
-            reinterpret_cast<u32x2 *>(t.codes)[i] = packed;
-            t.scales[i] = (uint8_t)out_code;
+            codes4 |= out_code << (8 * k);
             terr[k] = (double)out_err;
         }
     }
-    const double total = tensor_sum(2, terr);
-    if (tid == 0) {
+#pragma unroll
+    for (int pk = 0; pk < kPackets; ++pk) {
+        // streaming stores (the outputs are not read again here).  A packet with all its kX blocks present and
+        // the output addresses aligned for it: the 8 kX code bytes in 16-byte pieces, the kX scale bytes in one piece.
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        const uint32_t b0 = blk(pk * kX);
+        const bool whole = b0 + (uint32_t)kX <= t.nblk;
+        uint8_t *cp = t.codes + (size_t)b0 * 8;
+        uint8_t *sp = t.scales + b0;
+        const uint32_t (*nb)[2] = nibs + pk * kX;
+        const uint32_t sc = codes4 >> (8 * pk * kX);
+        if (kX >= 2 && whole && (reinterpret_cast<uintptr_t>(t.codes) & 15u) == 0u) {
+#pragma unroll
+            for (int k = 0; k < kX; k += 2)
+                __builtin_nontemporal_store(u32x4{nb[k][0], nb[k][1], nb[k + (kX >= 2 ? 1 : 0)][0], nb[k + (kX >= 2 ? 1 : 0)][1]},
+                                            reinterpret_cast<u32x4 *>(cp) + k / 2);
+        } else {
+#pragma unroll
+            for (int k = 0; k < kX; ++k)
+                if (b0 + (uint32_t)k < t.nblk)
+                    __builtin_nontemporal_store(u32x2{nb[k][0], nb[k][1]}, reinterpret_cast<u32x2 *>(cp) + k);
+        }
+        if (kX == 4 && whole && (reinterpret_cast<uintptr_t>(t.scales) & 3u) == 0u) {
+            __builtin_nontemporal_store(sc, reinterpret_cast<uint32_t *>(sp));
+        } else if (kX == 2 && whole && (reinterpret_cast<uintptr_t>(t.scales) & 1u) == 0u) {
+            __builtin_nontemporal_store((uint16_t)sc, reinterpret_cast<uint16_t *>(sp));
+        } else {
+#pragma unroll
+            for (int k = 0; k < kX; ++k)
+                if (b0 + (uint32_t)k < t.nblk) __builtin_nontemporal_store((uint8_t)(sc >> (8 * k)), sp + k);
+        }
+    }
+    wave_sum_to_lds(2, terr);
+    __syncthreads();
+    if (wave != 0) return;
+    // ---- error sum and status: workgroup 0 collects
+    double total = workgroup_sum(2);
+    bool ok = true;
+    if (grid.G > 1u) {
+        if (t.sse) ok = resident_collect_sum(grid, kResErr1, total);
+        if (ok && grid.g != 0u) return;
+    }
+    if (lane == 0) {
+        if (!ok) { give_up(); return; }
         if (t.sse) *t.sse = total;
         if (t.status) *t.status = (amax_bits >= 0x7F800000u ? SOAR_STATUS_NONFINITE : 0) | (allzero ? SOAR_STATUS_ALLZERO : 0);
         if (METHOD == SOAR_METHOD_RTN) *t.gscale = allzero ? 1.0f : alpha0;
