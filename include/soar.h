@@ -11,10 +11,20 @@
  *
  * Conventions common to all entry points
  *   - every pointer whose name starts with d_ is DEVICE memory owned by the
- *     caller; the library allocates nothing persistent and frees nothing;
+ *     caller; the library allocates no device memory and frees nothing.  What it
+ *     owns, per GPU and until the process ends: the fixed array inside its device
+ *     image that soar_quantize_static uses, four diagnostic counters, and -- created
+ *     by the first batch call that is spread over two streams (see `streams`) -- one
+ *     internal stream of default priority with two events;
  *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns without synchronising; results
  *     (global scale, error, data-dependent status) stay in device memory;
+ *   - the quantize / dequantize / error entry points may be called from several
+ *     host threads at once, each call with its own workspace and outputs; the
+ *     timing and statistics switches are process-wide and not thread-safe;
+ *   - inputs whose largest magnitude is below 2^-60 underflow inside the formulas
+ *     (products w*q, alpha*Delta): both the library and its reference follow
+ *     IEEE binary32 arithmetic there, but the results are not specified;
  *   - weights are row-major, `rows x cols`, leading dimension `ld_elems` >= cols
  *     (in elements); a block is 16 consecutive elements of a row, so
  *     cols % 16 == 0 is required; the weight base address must be 16-byte
@@ -113,7 +123,11 @@ typedef struct {
     int32_t  streams;        /* soar_quantize_batch: 0 = library default (launch
                                 groups alternate between the caller's stream and one
                                 internal stream, forked and joined by events);
-                                1 = everything on the caller's stream             */
+                                1 = everything on the caller's stream.  Only calls
+                                with streams = 1 (or that stay on one stream anyway:
+                                one launch group) may be captured into a HIP graph:
+                                the internal stream is shared by all callers, and a
+                                capture that pulls it in would swallow their work  */
     int32_t  dd_mode;        /* soar_dd_mode; dss_radius is ignored for BRACKET     */
     int32_t  resident;       /* soar_resident_mode: may one tensor handed over alone (single-
                                 step settings, tiles_per_wg 0, at most 4096 blocks per compute
@@ -185,7 +199,10 @@ size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *param
  * d_scales       out  rows*cols/16 bytes
  * d_global_scale out  1 float: alpha (1.0 for an all-zero tensor)
  * d_sse          out  1 double, may be NULL: sum over blocks of the Eq. 8 error
- *                     of the emitted codes and scales (= Eq. 4)
+ *                     of the emitted codes and scales (= Eq. 4).  The order of the
+ *                     binary64 additions follows the launch shape: bit-identical
+ *                     from call to call for a fixed tiles_per_wg and path (one
+ *                     launch / three passes), equal to within 1e-12 otherwise
  * d_status       out  1 int32, may be NULL: SOAR_STATUS_* bits
  * d_workspace    tmp  >= soar_workspace_bytes(), 256-byte aligned; calls that
  *                     share a workspace must be ordered on one stream
@@ -446,6 +463,15 @@ soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *la
  */
 soar_status soar_search_stats_enable(int enable);
 soar_status soar_search_stats_read(int64_t counts[4]);
+
+/*
+ * For tests: the counting plan of the kernels' "last workgroup of a tensor finishes the reduction"
+ * hand-off (host arithmetic only, no GPU needed).  Of a tensor's n_workgroups workgroups, workgroup w
+ * counts itself in on first-level counter out[1] of out[0] counters in use, which out[2] workgroups
+ * share; the workgroup that brings a first-level counter to its out[2] counts on the top counter, and
+ * the one that brings that to out[0] is the last.  Leaves `out` untouched on a bad argument.
+ */
+void soar_debug_arrival_plan(uint32_t n_workgroups, uint32_t workgroup, uint32_t out[3]);
 
 const char *soar_status_string(soar_status s);
 uint32_t    soar_version(void);

@@ -37,7 +37,7 @@ EXPORTS = (
     "soar_mxfp4_dequantize_batch",
     "soar_mxfp4_quantize_batch", "soar_mxfp4_batch_workspace_bytes",
     "soar_kernel_timing_enable", "soar_kernel_timing_read", "soar_search_stats_enable", "soar_search_stats_read",
-    "soar_status_string", "soar_version",
+    "soar_debug_arrival_plan", "soar_status_string", "soar_version",
 )
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -162,6 +162,8 @@ def lib():
     L.soar_search_stats_enable.restype = i32
     L.soar_search_stats_read.argtypes = [C.POINTER(i64)]
     L.soar_search_stats_read.restype = i32
+    L.soar_debug_arrival_plan.argtypes = [C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]
+    L.soar_debug_arrival_plan.restype = None
     L.soar_status_string.argtypes = [i32]
     L.soar_status_string.restype = C.c_char_p
     L.soar_version.argtypes = []
@@ -361,6 +363,13 @@ def soar_search_stats_read() -> dict:
     if rc != SOAR_OK:
         raise SoarError(rc, "soar_search_stats_read")
     return {"blocks": c[0], "blocks_handed_over": c[1], "wave_steps": c[2], "wave_steps_with_hand_over": c[3]}
+
+
+def soar_debug_arrival_plan(n_workgroups: int, workgroup: int):
+    """(counters in use, this workgroup's counter, workgroups sharing it) of the kernels' arrival counting"""
+    out = (C.c_uint32 * 3)(0xFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF)
+    lib().soar_debug_arrival_plan(n_workgroups, workgroup, out)
+    return out[0], out[1], out[2]
 
 
 def soar_version() -> int:

@@ -413,23 +413,50 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t m)
 // back with agent-scope atomic loads.  Arrival is counted on two levels (kSlots
 // first-level counters, one top counter) because read-modify-writes on a single
 // address serialise at roughly ten nanoseconds each.
+//
+// What the hand-off rests on (stronger than the HIP memory model's relaxed atomics promise by
+// themselves; true of gfx950 and of the code the compiler emits for these builtins):
+//  (1) an agent-scope atomic store or read-modify-write is performed at the memory side, beyond the
+//      per-XCD L2, and the wave's vmcnt counts it until it has been performed there; s_waitcnt(0)
+//      therefore returns only when everything the lane published is visible to every workgroup;
+//  (2) the compiler keeps the order publish -> s_waitcnt -> count: the workgroup-scope release fence
+//      in between forbids moving the stores below it;
+//  (3) ONE lane publishes and counts (the publishing lane's own vmcnt is the one that is waited on);
+//      a workgroup whose publishing is spread over lanes must bring them together (a workgroup barrier,
+//      whose stores have then completed per lane) before the counting lane counts;
+//  (4) the reader's agent-scope atomic loads are issued after its own fetch_add has returned (its
+//      result decides the branch they sit in) and bypass the non-coherent caches.
+// The counting itself is plain arithmetic, stated separately so that it can be checked on the host:
+struct ArrivalPlan {
+    uint32_t ns;         // first-level counters in use
+    uint32_t slot;       // the one this workgroup counts on
+    uint32_t expected;   // how many workgroups count on that one
+};
+__host__ __device__ inline ArrivalPlan arrival_plan(uint32_t G, uint32_t lwg)
+{
+    ArrivalPlan p;
+    p.ns = G < (uint32_t)kSlots ? G : (uint32_t)kSlots;
+    p.slot = lwg % p.ns;
+    p.expected = (G - p.slot + p.ns - 1) / p.ns;      // workgroups lwg' < G with lwg' % ns == slot
+    return p;
+}
+
 __device__ __forceinline__ void publish(double *p, double v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// called by one lane of the workgroup; true for exactly one of the tensor's G workgroups
+// called by one lane of the workgroup -- the lane that published; true for exactly one of the tensor's
+// G workgroups: the one whose increment completes its first-level counter and then the top counter
 __device__ __forceinline__ bool arrive_is_last(uint32_t *slots, uint32_t *top, uint32_t G, uint32_t lwg)
 {
-    const uint32_t ns = G < (uint32_t)kSlots ? G : (uint32_t)kSlots;
-    const uint32_t slot = lwg % ns;
-    const uint32_t expected = (G - slot + ns - 1) / ns;
+    const ArrivalPlan plan = arrival_plan(G, lwg);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);          // what this lane published has completed
-    uint32_t t = __hip_atomic_fetch_add(slots + slot * kSlotStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (t != expected - 1) return false;
+    uint32_t t = __hip_atomic_fetch_add(slots + plan.slot * kSlotStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t != plan.expected - 1) return false;
     uint32_t t2 = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return t2 == ns - 1;
+    return t2 == plan.ns - 1;
 }
 
 // the last workgroup puts the counters back to zero for the next launch

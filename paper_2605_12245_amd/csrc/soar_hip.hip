@@ -347,18 +347,38 @@ size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs)
     return (groups > 1 ? kLanes : 1) * lane_workspace_bytes(most);
 }
 
-hipStream_t aux_stream()
-{
-    // one per device, created on first use, default priority, never destroyed
-    static hipStream_t streams[64] = {};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-    if (!streams[dev]) {
-        hipStream_t st = nullptr;
-        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        streams[dev] = st;
+// What a batch of two or more launch groups needs beside the caller's stream: one stream per GPU
+// (default priority) and the two events that fork it off the caller's stream and join it back.  Created
+// on the first such call on a device, under std::call_once, shared by all callers and never destroyed.
+// An event is recorded and waited for under the lock, so that two host threads cannot wait for each
+// other's record.
+struct SecondLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    std::mutex mu;
+    bool usable = false;
+
+    // `from` -> `to`: work enqueued on `to` after this call starts after what `from` holds now
+    bool order(hipEvent_t ev, hipStream_t from, hipStream_t to)
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        return hipEventRecord(ev, from) == hipSuccess && hipStreamWaitEvent(to, ev, 0) == hipSuccess;
     }
-    return streams[dev];
+};
+
+SecondLane *second_lane()
+{
+    static std::once_flag once[kMaxDevices];
+    static SecondLane lanes[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::call_once(once[dev], [dev] {
+        SecondLane &l = lanes[dev];
+        l.usable = hipStreamCreateWithFlags(&l.stream, hipStreamNonBlocking) == hipSuccess &&
+                   hipEventCreateWithFlags(&l.fork, hipEventDisableTiming) == hipSuccess &&
+                   hipEventCreateWithFlags(&l.join, hipEventDisableTiming) == hipSuccess;
+    });
+    return lanes[dev].usable ? &lanes[dev] : nullptr;
 }
 
 template <int DT>
@@ -483,15 +503,11 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     char *base = static_cast<char *>(d_workspace);
 
     hipStream_t lane_stream[kLanes] = {st, st};
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    SecondLane *second = nullptr;
     if (lanes > 1) {
-        lane_stream[1] = aux_stream();
-        if (!lane_stream[1]) return SOAR_ERR_HIP;
-        if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return SOAR_ERR_HIP;
-        if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
-            (void)hipEventDestroy(ev_fork);
-            return SOAR_ERR_HIP;
-        }
+        second = second_lane();
+        if (!second) return SOAR_ERR_HIP;
+        lane_stream[1] = second->stream;
     }
     soar_status result = SOAR_OK;
     {
@@ -501,10 +517,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
         }
     }
-    if (lanes > 1 && result == SOAR_OK) {
-        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(lane_stream[1], ev_fork, 0) != hipSuccess)
-            result = SOAR_ERR_HIP;
-    }
+    if (lanes > 1 && result == SOAR_OK && !second->order(second->fork, st, lane_stream[1])) result = SOAR_ERR_HIP;
     int32_t g = 0;
     for (int32_t i = 0; i < n && result == SOAR_OK; ++g) {
         const int32_t j = group_end(n, descs, i);
@@ -558,13 +571,8 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
                                                  : launch_group<SOAR_FP32>(b, wg, params->method, lane_stream[lane]);
         i = j;
     }
-    if (lanes > 1) {
-        // always join, also after a failed launch, so that the caller's stream stays ordered
-        if (hipEventRecord(ev_join, lane_stream[1]) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess)
-            result = SOAR_ERR_HIP;
-        (void)hipEventDestroy(ev_fork);
-        (void)hipEventDestroy(ev_join);
-    }
+    // always join, also after a failed launch, so that the caller's stream stays ordered
+    if (lanes > 1 && !second->order(second->join, lane_stream[1], st)) result = SOAR_ERR_HIP;
     return result;
 }
 
@@ -904,15 +912,11 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
     // launch groups alternate between the caller's stream and one internal stream (forked and joined with
     // events), each with its own control slots, so that the ramp and the tail of one launch overlap another
     hipStream_t lane_stream[kLanes] = {st, st};
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    SecondLane *second = nullptr;
     if (lanes > 1) {
-        lane_stream[1] = aux_stream();
-        if (!lane_stream[1]) return SOAR_ERR_HIP;
-        if (hipEventCreateWithFlags(&ev_fork, hipEventDisableTiming) != hipSuccess) return SOAR_ERR_HIP;
-        if (hipEventCreateWithFlags(&ev_join, hipEventDisableTiming) != hipSuccess) {
-            (void)hipEventDestroy(ev_fork);
-            return SOAR_ERR_HIP;
-        }
+        second = second_lane();
+        if (!second) return SOAR_ERR_HIP;
+        lane_stream[1] = second->stream;
     }
     soar_status result = SOAR_OK;
     {
@@ -920,10 +924,7 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
         hipLaunchKernelGGL(k_init, dim3(lanes * slots * kInitSplit), dim3(kWG), 0, st, base);
         if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
     }
-    if (lanes > 1 && result == SOAR_OK) {
-        if (hipEventRecord(ev_fork, st) != hipSuccess || hipStreamWaitEvent(lane_stream[1], ev_fork, 0) != hipSuccess)
-            result = SOAR_ERR_HIP;
-    }
+    if (lanes > 1 && result == SOAR_OK && !second->order(second->fork, st, lane_stream[1])) result = SOAR_ERR_HIP;
     const bool two_pass = params->dss && params->single_pass == 0 && params->n_beta >= 4 && params->n_beta <= kMaxListBeta;
     const size_t lds = ((size_t)params->n_beta * 4 + 255) / 256 * 256 + (two_pass ? (size_t)params->n_beta * kWG : 0);
     // consecutive tensors of one element type share a launch (up to kGroupMax); every kernel leaves the
@@ -984,13 +985,8 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
         if (hipGetLastError() != hipSuccess) result = SOAR_ERR_HIP;
         i = j;
     }
-    if (lanes > 1) {
-        // always join, also after a failed launch, so that the caller's stream stays ordered
-        if (hipEventRecord(ev_join, lane_stream[1]) != hipSuccess || hipStreamWaitEvent(st, ev_join, 0) != hipSuccess)
-            result = SOAR_ERR_HIP;
-        (void)hipEventDestroy(ev_fork);
-        (void)hipEventDestroy(ev_join);
-    }
+    // always join, also after a failed launch, so that the caller's stream stays ordered
+    if (lanes > 1 && !second->order(second->join, lane_stream[1], st)) result = SOAR_ERR_HIP;
     return result;
 }
 
@@ -1107,6 +1103,15 @@ soar_status soar_kernel_timing_read(int kernel_id, double *total_ms, int64_t *la
     *total_ms = sum;
     *launches = (int64_t)g_timing.ev[kernel_id].size();
     return SOAR_OK;
+}
+
+void soar_debug_arrival_plan(uint32_t n_workgroups, uint32_t workgroup, uint32_t out[3])
+{
+    if (!out || n_workgroups == 0 || workgroup >= n_workgroups) return;
+    const ArrivalPlan p = arrival_plan(n_workgroups, workgroup);
+    out[0] = p.ns;
+    out[1] = p.slot;
+    out[2] = p.expected;
 }
 
 soar_status soar_search_stats_enable(int enable)

@@ -40,6 +40,7 @@ struct TileTree {
 // largest E4M3 code in [0x01, 0x7E] whose value does not exceed y (0x01 if none does)
 __device__ __forceinline__ int e4m3_floor_code(float y)
 {
+    if (!(y > 0.0f)) return (int)kE4M3Min;                  // zero, negative, NaN
     const int normal = (int)(__float_as_uint(y) >> 20) - (120 << 3);
     const int sub = (int)(fminf(y, 1.0f) * 512.0f);
     const int code = (y >= 0x1p-6f) ? normal : sub;

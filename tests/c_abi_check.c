@@ -23,7 +23,7 @@ int main(void)
         (any_fn)soar_recon_error_batch, (any_fn)soar_e2m1_round_f32, (any_fn)soar_e4m3_project_f32,
         (any_fn)soar_rcp_midrange_f32, (any_fn)soar_mx_default_params, (any_fn)soar_mxfp4_workspace_bytes,
         (any_fn)soar_mxfp4_quantize, (any_fn)soar_mxfp4_quantize_batch, (any_fn)soar_mxfp4_batch_workspace_bytes,
-        (any_fn)soar_mxfp4_dequantize, (any_fn)soar_mxfp4_dequantize_batch, (any_fn)soar_kernel_timing_enable, (any_fn)soar_kernel_timing_read, (any_fn)soar_search_stats_enable, (any_fn)soar_search_stats_read,
+        (any_fn)soar_mxfp4_dequantize, (any_fn)soar_mxfp4_dequantize_batch, (any_fn)soar_kernel_timing_enable, (any_fn)soar_kernel_timing_read, (any_fn)soar_search_stats_enable, (any_fn)soar_search_stats_read, (any_fn)soar_debug_arrival_plan,
         (any_fn)soar_status_string, (any_fn)soar_version,
     };
     size_t k;

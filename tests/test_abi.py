@@ -224,3 +224,46 @@ def test_missing_library_raises_instead_of_falling_back(monkeypatch):
         B.lib()
     with pytest.raises(RuntimeError):
         B.soar_default_params()
+
+
+def test_arrival_counting_names_exactly_one_last_workgroup():
+    """The two-level arrival counting of the kernels' hand-off ("the last workgroup of a tensor finishes the
+    reduction"), modelled on the host with the library's own plan: for every number of workgroups and any
+    order of arrival, every workgroup has a first-level counter, the counters' shares add up to the
+    workgroups, exactly one arrival completes the top counter, and it is the last one to arrive."""
+    import random
+    rng = random.Random(5)
+    sizes = list(range(1, 200)) + [255, 256, 257, 1000, 4095, 4096, 4097, 16383, 16384] + [rng.randrange(200, 16384) for _ in range(40)]
+    for G in sizes:
+        plans = [B.soar_debug_arrival_plan(G, w) for w in range(G)] if G <= 4097 else None
+        if plans is None:                         # large: the plan is periodic in the workgroup number; sample it
+            ns = min(G, 64)
+            base = [B.soar_debug_arrival_plan(G, w) for w in range(ns)]
+            plans = [base[w % ns] for w in range(G)]
+            for w in rng.sample(range(G), 64):
+                assert B.soar_debug_arrival_plan(G, w) == plans[w]
+        ns = plans[0][0]
+        assert ns == min(G, 64) and all(p[0] == ns for p in plans)
+        share = {}
+        for w, (_, slot, expected) in enumerate(plans):
+            assert slot < ns and expected >= 1
+            share.setdefault(slot, set()).add(expected)
+        assert len(share) == ns and all(len(v) == 1 for v in share.values())
+        assert sum(next(iter(v)) for v in share.values()) == G
+        for _ in range(3 if G < 300 else 1):
+            order = list(range(G))
+            rng.shuffle(order)
+            slots, top, last = [0] * ns, 0, []
+            for w in order:
+                _, slot, expected = plans[w]
+                t = slots[slot]
+                slots[slot] += 1
+                if t != expected - 1:
+                    continue
+                t2 = top
+                top += 1
+                if t2 == ns - 1:
+                    last.append(w)
+            assert last == [order[-1]], (G, last)
+            assert slots == [next(iter(share[k])) for k in range(ns)] and top == ns
+    assert B.soar_debug_arrival_plan(0, 0) == (0xFFFFFFFF,) * 3 and B.soar_debug_arrival_plan(5, 5) == (0xFFFFFFFF,) * 3
