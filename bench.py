@@ -73,7 +73,7 @@ def iter_lane_ops_per_block_beta(ncand):
 
 
 def iterated_params(B, args, streams):
-    stop = 0.0 if args.no_early_stop else 1e-3
+    stop = 0.0 if args.no_early_stop else args.early_stop_rel
     if args.algorithm == "paper":
         p = B.soar_paper_params(iters=args.iters or None, early_stop_rel=stop, tiles_per_wg=args.tpw, streams=streams)
     else:
@@ -107,6 +107,8 @@ def parse_args():
                          "traffic scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--iters", type=int, default=0, help="--algorithm paper: override T")
     ap.add_argument("--no-early-stop", action="store_true", help="--algorithm paper: run all T iterations")
+    ap.add_argument("--early-stop-rel", type=float, default=1e-3,
+                    help="iterated algorithms: stop after an iteration that gains less than this fraction (Appendix B.3: 1e-3)")
     ap.add_argument("--dtype", choices=["bf16", "fp32"], default="bf16",
                     help="element type of the weights (NVFP4 algorithms only; every byte figure scales with it)")
     ap.add_argument("--graph", action="store_true",
@@ -278,11 +280,13 @@ def main():
             # no search: an iteration reads the weights and the carried ratio and writes ratio, codes and scale
             per_w = 2.0 + 0.25 + 0.25 + 0.5625
             gbs = block_iters * 16 * per_w / t_iter / 1e9
-            roofline = {"kernel": "k_iter", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            roofline = {"kernel": "k_cjso", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": gbs / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_weight_and_iteration": per_w,
                         "block_iterations_per_step": block_iters,
-                        "launches_per_step": kernels["iter"]["launches"] / n_prof,
-                        "note": "all k_iter launches of a step together; HIP-event durations on the launch stream"}
+                        "timed_loops_per_step": kernels["iter"]["launches"] / n_prof,
+                        "note": "all iteration launches of a step together (launches of tensors that have stopped return "
+                                "at once): one HIP-event bracket per launch group round its T launches, on the launch "
+                                "stream, single-stream pass"}
         else:
             roofline = {"kernel": "k_iter", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
@@ -290,9 +294,10 @@ def main():
                         "frac_of_unpacked_issue_rate": lane_ops / t_iter / VALU_LANE_OPS_PEAK,
                         "flops_per_block_beta": iter_flops_per_block_beta(ncand),
                         "block_iterations_per_step": block_iters,
-                        "launches_per_step": kernels["iter"]["launches"] / n_prof,
+                        "timed_loops_per_step": kernels["iter"]["launches"] / n_prof,
                         "note": "all k_iter launches of a step together (launches of tensors that have stopped "
-                                "return at once); HIP-event durations on the launch stream, single-stream pass"}
+                                "return at once): one HIP-event bracket per launch group round its T launches, on "
+                                "the launch stream, single-stream pass"}
     elif not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
         p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,

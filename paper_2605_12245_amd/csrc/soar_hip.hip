@@ -302,12 +302,20 @@ soar_status validate_tensor(const soar_tensor_desc &d, const soar_params *params
 int64_t weight_bytes(const soar_tensor_desc &d) { return d.rows * d.cols * (d.dtype == SOAR_BF16 ? 2 : 4); }
 
 constexpr int64_t kOnePassByteCap = (int64_t)1 << 29;    // larger launches gain nothing more (measured: 2^29 .. 2^31)
-int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
+
+// bytes of weights one launch may cover (beyond its first tensor)
+int64_t group_byte_cap(const soar_tensor_desc *descs, const soar_params *params)
+{
+    // with the maximum supplied there is one pass only: nothing to keep in the last-level cache
+    if (descs[0].d_amax_in) return kOnePassByteCap;
+    (void)params;
+    return kGroupByteCap;      // a group stays in the 256 MiB last-level cache from pass to pass, iteration to iteration
+}
+
+int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first, int64_t cap)
 {
     int64_t bytes = weight_bytes(descs[first]);
     int32_t j = first + 1;
-    // with the maximum supplied there is one pass only: nothing to keep in the last-level cache
-    const int64_t cap = descs[first].d_amax_in ? kOnePassByteCap : kGroupByteCap;
     while (j < n && j - first < kGroupMax && descs[j].dtype == descs[first].dtype &&
            bytes + weight_bytes(descs[j]) <= cap) {
         bytes += weight_bytes(descs[j]);
@@ -317,12 +325,12 @@ int32_t group_end(int32_t n, const soar_tensor_desc *descs, int32_t first)
 }
 
 // most per-block workspace any one launch of the batch needs
-size_t max_group_per_block_bytes(int32_t n, const soar_tensor_desc *descs, int32_t *n_groups)
+size_t max_group_per_block_bytes(int32_t n, const soar_tensor_desc *descs, int64_t cap, int32_t *n_groups)
 {
     size_t most = 0;
     int32_t groups = 0;
     for (int32_t i = 0; i < n;) {
-        const int32_t j = group_end(n, descs, i);
+        const int32_t j = group_end(n, descs, i, cap);
         size_t sum = 0;
         for (int32_t k = i; k < j; ++k) sum += per_block_bytes(descs[k].rows, descs[k].cols);
         if (sum > most) most = sum;
@@ -340,10 +348,10 @@ size_t max_group_per_block_bytes(int32_t n, const soar_tensor_desc *descs, int32
 
 size_t lane_workspace_bytes(size_t group_per_block) { return (size_t)kGroupMax * kSlotBytes + group_per_block; }
 
-size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs)
+size_t batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs, const soar_params *params)
 {
     int32_t groups = 0;
-    const size_t most = max_group_per_block_bytes(n, descs, &groups);
+    const size_t most = max_group_per_block_bytes(n, descs, group_byte_cap(descs, params), &groups);
     return (groups > 1 ? kLanes : 1) * lane_workspace_bytes(most);
 }
 
@@ -429,10 +437,13 @@ soar_status launch_group_iter(Batch &b, uint32_t total_wg, int iters, hipStream_
         hipLaunchKernelGGL(k_iter_init<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     }
+    // one pair of timing events round all iterations of the group: launches that find their tensors stopped
+    // last about a microsecond, less than what an event pair of their own would add
+    ScopedTimer t(SOAR_KERNEL_ITER, st);
     for (int it = 0; it < iters; ++it) {
         b.iter_t = it;
-        ScopedTimer t(SOAR_KERNEL_ITER, st);
-        hipLaunchKernelGGL(k_iter<DT>, dim3(total_wg), dim3(kWG), iter_lds_bytes(b), st, b);
+        if (b.arm == SOAR_METHOD_CJSO_ONLY) hipLaunchKernelGGL(k_cjso<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        else hipLaunchKernelGGL(k_iter<DT>, dim3(total_wg), dim3(kWG), iter_lds_bytes(b), st, b);
         SOAR_LAUNCH_CHECK();
     }
     return SOAR_OK;
@@ -459,7 +470,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
 
     if (n == 0) return SOAR_OK;
     if (!d_workspace || reinterpret_cast<uintptr_t>(d_workspace) % 256 != 0) return SOAR_ERR_WORKSPACE;
-    if (workspace_bytes < batch_workspace_bytes(n, descs)) return SOAR_ERR_WORKSPACE;
+    if (workspace_bytes < batch_workspace_bytes(n, descs, params)) return SOAR_ERR_WORKSPACE;
 
     // one tensor, single-step settings, default launch shape: the whole path in one launch that keeps the
     // tensor in registers, if its grid fits the GPU (see k_resident); only the slot's flag words are used
@@ -498,7 +509,8 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     }
 
     int32_t n_groups = 0;
-    const size_t lane_bytes = lane_workspace_bytes(max_group_per_block_bytes(n, descs, &n_groups));
+    const int64_t cap = group_byte_cap(descs, params);
+    const size_t lane_bytes = lane_workspace_bytes(max_group_per_block_bytes(n, descs, cap, &n_groups));
     const int lanes = (n_groups > 1 && params->streams != 1) ? kLanes : 1;
     char *base = static_cast<char *>(d_workspace);
 
@@ -520,7 +532,7 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     if (lanes > 1 && result == SOAR_OK && !second->order(second->fork, st, lane_stream[1])) result = SOAR_ERR_HIP;
     int32_t g = 0;
     for (int32_t i = 0; i < n && result == SOAR_OK; ++g) {
-        const int32_t j = group_end(n, descs, i);
+        const int32_t j = group_end(n, descs, i, cap);
         const int lane = g % lanes;
         char *lane_base = base + (size_t)lane * lane_bytes;
         Batch b;
@@ -723,7 +735,7 @@ size_t soar_batch_workspace_bytes(int32_t n, const soar_tensor_desc *descs, cons
     if (n <= 0 || !descs || !valid_params(params)) return 0;
     for (int32_t k = 0; k < n; ++k)
         if (check_shape(descs[k].rows, descs[k].cols, descs[k].ld_elems) != SOAR_OK) return 0;
-    return batch_workspace_bytes(n, descs);
+    return batch_workspace_bytes(n, descs, params);
 }
 
 soar_status soar_quantize(const void *d_w, soar_dtype dtype, int64_t rows, int64_t cols, int64_t ld_elems,

@@ -37,6 +37,68 @@ struct TileTree {
     }
 };
 
+// The same three sums for the memory-bound kernels, at a fraction of the cross-lane work: what a block
+// contributes -- a = sum w q, b = sum q^2, its stored scale d and its error, four floats -- is staged in LDS
+// for up to kStage consecutive tiles; lane t then forms the binary64 terms a d, b d^2, err of the adjacent
+// blocks t*T .. t*T+T-1 (exact products, wherever they are formed), folds them in registers, and ONE wave
+// tree, the four waves and the binary-counter stack finish the group -- the adjacent-pair tree again
+// (k_stats does the same for its two sums).  Per group of T tiles: stage() once per tile by every lane,
+// then close() by every lane; after the last group lane 0 holds the sums (N, M, error) in wg[].
+struct StagedTree {
+    float4 *s_blocks;        // [kStage * kWG]: a, b, d, err; zeros for a block that does not exist
+    double (*s_wave)[4];     // [3][4]
+    double (*s_stack)[32];   // [3][32]
+    double wg[3] = {};
+    __device__ __forceinline__ void stage(uint32_t kk, float a, float b, float d, float err)
+    {
+        s_blocks[kk * kWG + threadIdx.x] = make_float4(a, b, d, err);
+    }
+    static __device__ __forceinline__ void terms(const float4 &x, double v[3])
+    {
+        v[0] = (double)x.x * (double)x.z;
+        v[1] = ((double)x.y * (double)x.z) * (double)x.z;
+        v[2] = (double)x.w;
+    }
+    // group `k` of the workgroup, T tiles staged (T a power of two <= kStage)
+    __device__ __forceinline__ void close(uint32_t k, uint32_t T)
+    {
+        __syncthreads();
+        const float4 *x = s_blocks + threadIdx.x * T;
+        double v[3];
+        terms(x[0], v);
+        if (T >= 2) {
+            double u[3];
+            terms(x[1], u);
+#pragma unroll
+            for (int n = 0; n < 3; ++n) v[n] = v[n] + u[n];
+        }
+        if (T == 4) {
+            double u[3], z[3];
+            terms(x[2], u);
+            terms(x[3], z);
+#pragma unroll
+            for (int n = 0; n < 3; ++n) v[n] = v[n] + (u[n] + z[n]);
+        }
+#pragma unroll
+        for (int n = 0; n < 3; ++n) v[n] = wave_pair_tree(v[n]);
+        if ((threadIdx.x & 63) == 0)
+#pragma unroll
+            for (int n = 0; n < 3; ++n) s_wave[n][threadIdx.x >> 6] = v[n];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int n = 0; n < 3; ++n) {
+                double y = (s_wave[n][0] + s_wave[n][1]) + (s_wave[n][2] + s_wave[n][3]);
+                uint32_t lvl = 0;
+                while ((k >> lvl) & 1u) { y = s_stack[n][lvl] + y; ++lvl; }
+                s_stack[n][lvl] = y;
+                wg[n] = y;
+            }
+        }
+    }
+};
+static_assert(kStage == 4, "StagedTree::close folds up to four tiles");
+
 // largest E4M3 code in [0x01, 0x7E] whose value does not exceed y (0x01 if none does)
 __device__ __forceinline__ int e4m3_floor_code(float y)
 {
@@ -225,10 +287,12 @@ __device__ __forceinline__ void joint_search_two_pass(const float w[16], float a
 template <int DT>
 __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
 {
+    __shared__ float4 s_blocks[kStage * kWG];
     __shared__ double s_wave[3][4];
     __shared__ double s_stack[3][32];
-    __shared__ double s_tree[kWG];
     __shared__ uint32_t s_last;
+    double *s_tree = reinterpret_cast<double *>(s_blocks);      // tree_of_partials, after the last group: kWG doubles
+    static_assert(sizeof(float4) * kStage >= sizeof(double), "s_tree fits s_blocks");
 
     uint32_t lwg;
     const Task t = batch.t[find_task(batch, lwg)];
@@ -238,28 +302,29 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
     const float alpha0 = f_of(amax_bits) / 2688.0f;
     const float alpha0_m = alpha0 * 6.0f;
 
-    TileTree<3> tree{s_wave, s_stack};
+    StagedTree tree{s_blocks, s_wave, s_stack};
     const uint32_t tile0 = lwg * t.tiles_per_wg;
-    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
-        const uint32_t i = (tile0 + k) * kWG + tid;
-        double term[3] = {0.0, 0.0, 0.0};
-        if (i < t.nblk) {
-            float rho = 0.0f;
-            if (!degenerate) {
-                float w[16], q[16];
-                uint32_t nib[2], c0;
-                float delta0, a, b;
-                load_block<DT>(t.w, block_offset(t, i), w);
-                block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
-                block_sums(w, q, a, b);
-                term[0] = (double)a * (double)delta0;
-                term[1] = ((double)b * (double)delta0) * (double)delta0;
-                term[2] = (double)block_error(w, q, alpha0 * delta0);
-                rho = (b == 0.0f || batch.arm == SOAR_METHOD_DSS_ONLY) ? -delta0 : a / b;
+    const uint32_t T = t.tiles_per_wg < (uint32_t)kStage ? t.tiles_per_wg : (uint32_t)kStage;   // power of two
+    for (uint32_t kg = 0; kg < t.tiles_per_wg; kg += T) {
+        for (uint32_t kk = 0; kk < T; ++kk) {
+            const uint32_t i = (tile0 + kg + kk) * kWG + tid;
+            float a = 0.0f, b = 0.0f, delta0 = 0.0f, err = 0.0f;
+            if (i < t.nblk) {
+                float rho = 0.0f;
+                if (!degenerate) {
+                    float w[16], q[16];
+                    uint32_t nib[2], c0;
+                    load_block<DT>(t.w, block_offset(t, i), w);
+                    block_init(w, alpha0, alpha0_m, c0, delta0, nib, q);
+                    block_sums(w, q, a, b);
+                    err = block_error(w, q, alpha0 * delta0);
+                    rho = (b == 0.0f || batch.arm == SOAR_METHOD_DSS_ONLY) ? -delta0 : a / b;
+                }
+                t.rho[i] = rho;
             }
-            t.rho[i] = rho;
+            tree.stage(kk, a, b, delta0, err);
         }
-        tree.add_tile(k, term);
+        tree.close(kg / T, T);
     }
     uint32_t *counters = t.counters + 1 * kSlots * kSlotStride;
     if (tid == 0) {
@@ -284,6 +349,32 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
         if (!degenerate && t.trace) t.trace[0] = E;
     }
     reset_counters(counters, &t.ctrl->top[1]);
+}
+
+// What the last workgroup of a tensor does after an iteration (one lane): the outputs that describe the
+// tensor, the early-stop decision and the global scale the next iteration starts from (Eq. 5).
+__device__ __forceinline__ void finish_iteration(const Batch &batch, const Task &t, double N, double M, double cur, float alpha,
+                                                 bool degenerate, bool allzero, bool dss_only)
+{
+    if (degenerate) {
+        *t.gscale = allzero ? 1.0f : __builtin_nanf("");
+        if (t.sse) *t.sse = allzero ? 0.0 : __builtin_nan("");
+        if (t.status) *t.status = allzero ? SOAR_STATUS_ALLZERO : SOAR_STATUS_NONFINITE;
+        if (t.iters_run) *t.iters_run = 0;
+    } else {
+        const double prev = t.ctrl->prev_sse;
+        *t.gscale = alpha;
+        if (t.sse) *t.sse = cur;
+        if (t.status) *t.status = 0;
+        if (t.iters_run) *t.iters_run = batch.iter_t + 1;
+        if (t.trace) t.trace[batch.iter_t + 1] = cur;
+        const bool stop = batch.early_stop_rel > 0.0f && (prev - cur) < (double)batch.early_stop_rel * prev;
+        t.ctrl->stopped = stop ? 1u : 0u;
+        t.ctrl->prev_sse = cur;
+        t.ctrl->alpha1 = (M > 0.0 && !dss_only) ? (float)(N / M) : alpha;      // Eq. 5 for the next iteration
+        t.ctrl->N = N;
+        t.ctrl->M = M;
+    }
 }
 
 // One iteration of Algorithm 1.  On entry ctrl->alpha1 holds the Eq. 5 global
@@ -326,7 +417,6 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     const float alpha = t.ctrl->alpha1;
     const bool bracket = batch.dd_mode == SOAR_DD_BRACKET;
     const int radius = batch.radius;
-    const bool one_scale = batch.arm == SOAR_METHOD_CJSO_ONLY;
     const bool two_pass = n_beta >= 4 && n_beta <= kMaxListBeta && !batch.full_search;
     const bool dss_only = batch.arm == SOAR_METHOD_DSS_ONLY;    // rho then always carries -Delta^d: the search centre
 
@@ -357,13 +447,7 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
                 const float s_first = alpha * (delta_star * s_beta[0]);
                 const float s_final = alpha * (delta_star * s_beta[n_beta - 1]);
                 const bool mid = ((__float_as_uint(s_first) >> 23) - 2u) < 250u && ((__float_as_uint(s_final) >> 23) - 2u) < 250u;
-                if (one_scale) {
-                    // Sec. 3.2 alone: the projected scale assigns the codes and is stored; nothing to search
-                    best_code = c0;
-                    const float sd = alpha * e4m3_value((uint32_t)c0);
-                    assign_codes(w, sd, best_nib, q);
-                    best_err = block_error(w, q, sd);
-                } else if (two_pass) {
+                if (two_pass) {
                     if (__builtin_amdgcn_ballot_w64(!mid) == 0ull)
                         joint_search_two_pass<true>(w, alpha, delta_star, s_beta, n_beta, bracket, c0, radius, s_list,
                                                     best_err, best_code, best_nib, q);
@@ -405,27 +489,85 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
     const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
     const double cur = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
-    if (tid == 0) {
-        if (degenerate) {
-            *t.gscale = allzero ? 1.0f : __builtin_nanf("");
-            if (t.sse) *t.sse = allzero ? 0.0 : __builtin_nan("");
-            if (t.status) *t.status = allzero ? SOAR_STATUS_ALLZERO : SOAR_STATUS_NONFINITE;
-            if (t.iters_run) *t.iters_run = 0;
-        } else {
-            const double prev = t.ctrl->prev_sse;
-            *t.gscale = alpha;
-            if (t.sse) *t.sse = cur;
-            if (t.status) *t.status = 0;
-            if (t.iters_run) *t.iters_run = batch.iter_t + 1;
-            if (t.trace) t.trace[batch.iter_t + 1] = cur;
-            const bool stop = batch.early_stop_rel > 0.0f && (prev - cur) < (double)batch.early_stop_rel * prev;
-            t.ctrl->stopped = stop ? 1u : 0u;
-            t.ctrl->prev_sse = cur;
-            t.ctrl->alpha1 = (M > 0.0 && !dss_only) ? (float)(N / M) : alpha;      // Eq. 5 for the next iteration
-            t.ctrl->N = N;
-            t.ctrl->M = M;
+    if (tid == 0) finish_iteration(batch, t, N, M, cur, alpha, degenerate, allzero, dss_only);
+    reset_counters(counters, &t.ctrl->top[2]);
+}
+
+// One iteration of the closed-form arm of the component study (Sec. 3.2 alone): no search.  Per block the
+// projected scale E4M3(Delta*) assigns the codes AND is stored; the codes' a/b and Eq. 5 terms are formed
+// for the next iteration as in k_iter, and the tensor is finished by finish_iteration.  The kernel is bound
+// by memory (weights and ratio read, ratio, codes and scale written), so it is built like k_stats: several
+// consecutive tiles per workgroup, the three sums through the staged tree, streaming stores for the outputs
+// (the weights and the ratio are read again by the next iteration and stay in the last-level cache).
+template <int DT>
+__global__ __launch_bounds__(kWG) void k_cjso(const Batch batch)
+{
+    __shared__ float4 s_blocks[kStage * kWG];
+    __shared__ double s_wave[3][4];
+    __shared__ double s_stack[3][32];
+    __shared__ uint32_t s_last;
+    double *s_tree = reinterpret_cast<double *>(s_blocks);      // tree_of_partials, after the last group: kWG doubles
+
+    uint32_t lwg;
+    const Task t = batch.t[find_task(batch, lwg)];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t amax_bits = t.ctrl->amax_bits;
+    const bool allzero = amax_bits == 0u;
+    const bool degenerate = allzero || amax_bits >= 0x7F800000u;
+    if (degenerate ? batch.iter_t != 0 : t.ctrl->stopped != 0u) return;     // uniform over the tensor's workgroups
+    const float alpha = t.ctrl->alpha1;
+
+    StagedTree tree{s_blocks, s_wave, s_stack};
+    const uint32_t tile0 = lwg * t.tiles_per_wg;
+    const uint32_t T = t.tiles_per_wg < (uint32_t)kStage ? t.tiles_per_wg : (uint32_t)kStage;   // power of two
+    for (uint32_t kg = 0; kg < t.tiles_per_wg; kg += T) {
+        for (uint32_t kk = 0; kk < T; ++kk) {
+            const uint32_t i = (tile0 + kg + kk) * kWG + tid;
+            float a = 0.0f, b = 0.0f, d = 0.0f, err = 0.0f;
+            if (i < t.nblk && amax_bits < 0x7F800000u) {
+                float w[16], q[16];
+                uint32_t nib[2] = {0u, 0u};
+                uint32_t code = kE4M3Min;
+                load_block<DT>(t.w, block_offset(t, i), w);
+                if (allzero) {
+                    float x[16];
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) x[j] = w[j];
+                    nib[0] = fp4x8(x);
+                    nib[1] = fp4x8(x + 8);
+                } else {
+                    const float rho = t.rho[i];
+                    const float delta_star = (rho < 0.0f) ? -rho : rho / alpha;          // Eq. 6
+                    code = e4m3_project(delta_star);
+                    d = e4m3_value(code);
+                    const float sd = alpha * d;
+                    assign_codes(w, sd, nib, q);
+                    block_sums(w, q, a, b);
+                    err = block_error(w, q, sd);
+                    t.rho[i] = (b == 0.0f) ? -d : a / b;
+                }
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 packed = {nib[0], nib[1]};
+                __builtin_nontemporal_store(packed, reinterpret_cast<u32x2 *>(t.codes) + i);
+                __builtin_nontemporal_store((uint8_t)code, t.scales + i);
+            }
+            tree.stage(kk, a, b, d, err);
         }
+        tree.close(kg / T, T);
     }
+    uint32_t *counters = t.counters + 2 * kSlots * kSlotStride;
+    if (tid == 0) {
+        publish(t.part + lwg, tree.wg[0]);
+        publish(t.part + kMaxPartials + lwg, tree.wg[1]);
+        publish(t.part + 2 * kMaxPartials + lwg, tree.wg[2]);
+        s_last = arrive_is_last(counters, &t.ctrl->top[2], t.n_wg, lwg) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
+    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
+    const double cur = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    if (tid == 0) finish_iteration(batch, t, N, M, cur, alpha, degenerate, allzero, false);
     reset_counters(counters, &t.ctrl->top[2]);
 }
 
