@@ -63,13 +63,40 @@ VALU_PEAK_TFLOPS = 157.3       # MI355X FP32 vector, published (packed FP32)
 VALU_LANE_OPS_PEAK = 256 * 4 * 16 * 2.4e9   # one non-packed 32-bit op per lane: CUs x SIMDs x lanes/clk x clock
 
 
-def iter_flops_per_block_beta(ncand):
-    return 16 + 16 + 16 + ncand * (16 * 2 + 16 * 2)
+def iter_flops_per_block_beta(ncand, nelem=16):
+    """floating-point operations the method's definition asks for per block and factor: nelem products w*r, and per
+    stored-scale candidate nelem fused residuals and nelem fused square-accumulates (2 operations each).  The
+    roundings onto E2M1 and the decoded values are conversions, not floating-point operations, and are not counted."""
+    return nelem + ncand * (nelem * 2 + nelem * 2)
 
 
-def iter_lane_ops_per_block_beta(ncand):
-    # the same work as machine operations: 16 mul, 8 two-element conversions each way, 32 fused ops per candidate
-    return 16 + 8 + 8 + ncand * 32
+def iter_lane_ops_per_block_beta(ncand, nelem=16):
+    """the plain loop as vector instructions per lane: nelem multiplications, nelem/2 two-element conversions each way,
+    2 nelem fused operations per candidate (a model: used where no counter run has measured the executed count)"""
+    return nelem + nelem // 2 + nelem // 2 + ncand * 2 * nelem
+
+
+def alu_roofline(kernel, algorithm, workload, dtype, search, layers, steps_blocks_factors, ncand, t_kernel, nelem=16):
+    """Roofline of an arithmetic-bound kernel: executed vector instructions per lane against the rate at which the
+    part issues them unpacked (256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit operation per lane and cycle; the
+    published 157.3 TFLOP/s is this rate x 2 for fused multiply-add x 2 for packed FP32, which this build does not
+    emit).  The executed count per (block, factor) comes from a SQ_INSTS_VALU counter run (profiles/pmc_table.json);
+    without one the plain loop's instruction count stands in and the line says so.  The method-definition
+    floating-point rate is reported beside it."""
+    e, why = pmc_entry(algorithm, workload, dtype, kernel, layers, search)
+    if e is not None and "valu_lane_insts_per_block_factor" in e:
+        per_step, source = e["valu_lane_insts_per_block_factor"], why
+    else:
+        per_step, source = iter_lane_ops_per_block_beta(ncand, nelem), "modelled (plain loop): " + why
+    lane_ops = steps_blocks_factors * per_step
+    flops = steps_blocks_factors * iter_flops_per_block_beta(ncand, nelem)
+    return {"kernel": kernel, "bound": "alu", "achieved": lane_ops / t_kernel / 1e12, "peak": VALU_LANE_OPS_PEAK / 1e12,
+            "unit": "T lane-op/s", "frac": lane_ops / t_kernel / VALU_LANE_OPS_PEAK, "traffic": None,
+            "executed_lane_insts_per_block_factor": per_step, "executed_count_source": source,
+            "method_flops_per_block_factor": iter_flops_per_block_beta(ncand, nelem),
+            "method_tflops": flops / t_kernel / 1e12,
+            "method_tflops_frac_of_packed_fma_peak": flops / t_kernel / 1e12 / VALU_PEAK_TFLOPS,
+            "block_factor_steps_per_step": steps_blocks_factors}
 
 
 def iterated_params(B, args, streams):
@@ -119,6 +146,9 @@ def parse_args():
                     help="with --reps: write a 1 GiB scratch buffer before every repetition (caches hold none of the input)")
     ap.add_argument("--per-tensor", action="store_true",
                     help="--algorithm dequantize / recon-error: one call per tensor instead of the batch entry point")
+    ap.add_argument("--search-stats", action="store_true",
+                    help="single-step: after the timed region, one more pass with the library's diagnostic counters on: how "
+                         "often the certified Eq. 8 search handed a block over to the exhaustive loop")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
@@ -272,10 +302,7 @@ def main():
         B.soar_kernel_timing_enable(False)
         ncand = 2 if params.dd_mode == B.SOAR_DD_BRACKET else 2 * params.dss_radius + 1
         block_iters = sum(it * (s.numel // 16) for it, s in zip(iters_run, specs))       # per step
-        flops = block_iters * params.n_beta * iter_flops_per_block_beta(ncand)
-        lane_ops = block_iters * params.n_beta * iter_lane_ops_per_block_beta(ncand)
         t_iter = kernels["iter"]["ms_per_step"] * 1e-3
-        achieved = flops / t_iter / 1e12
         if args.algorithm == "cjso-only":
             # no search: an iteration reads the weights and the carried ratio and writes ratio, codes and scale
             per_w = 2.0 + 0.25 + 0.25 + 0.5625
@@ -288,16 +315,12 @@ def main():
                                 "at once): one HIP-event bracket per launch group round its T launches, on the launch "
                                 "stream, single-stream pass"}
         else:
-            roofline = {"kernel": "k_iter", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS,
-                        "unit": "TFLOP/s", "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
-                        "lane_ops_per_s": lane_ops / t_iter, "lane_ops_peak_unpacked": VALU_LANE_OPS_PEAK,
-                        "frac_of_unpacked_issue_rate": lane_ops / t_iter / VALU_LANE_OPS_PEAK,
-                        "flops_per_block_beta": iter_flops_per_block_beta(ncand),
-                        "block_iterations_per_step": block_iters,
-                        "timed_loops_per_step": kernels["iter"]["launches"] / n_prof,
-                        "note": "all k_iter launches of a step together (launches of tensors that have stopped "
-                                "return at once): one HIP-event bracket per launch group round its T launches, on "
-                                "the launch stream, single-stream pass"}
+            roofline = alu_roofline("k_iter", args.algorithm, args.workload, args.dtype, args.search, args.layers,
+                                    block_iters * params.n_beta, ncand, t_iter)
+            roofline["timed_loops_per_step"] = kernels["iter"]["launches"] / n_prof
+            roofline["note"] = ("all k_iter launches of a step together (launches of tensors that have stopped return at "
+                                "once): one HIP-event bracket per launch group round its T launches, on the launch "
+                                "stream, single-stream pass")
     elif not args.no_kernel_timing:
         n_prof = min(args.steps, 5)
         p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,
@@ -327,7 +350,20 @@ def main():
                     "algorithmic_bytes_per_weight": per_elem[dom],
                     "weights_per_launch": E / (kernels[dom]["launches"] / n_prof),
                     "avg_launch_us": kernels[dom]["avg_us"],
-                    "note": "per-launch HIP-event durations on the launch stream, single-stream pass"}
+                    "note": "per-launch HIP-event durations on the launch stream, single-stream pass"
+                            + ("; the one-launch kernel reads the weights once, so its algorithmic bytes are those of the "
+                               "search pass alone; it is bound by its arithmetic and by two trips across the grid, "
+                               "not by memory" if dom == "resident" else "")}
+
+    # ---- diagnostics of the certified search (untimed pass, counters on)
+    search_stats = None
+    if args.search_stats and args.algorithm == "single-step":
+        B.soar_search_stats_enable(True)
+        B.quantize_batch(descs, params, ws)
+        c = B.soar_search_stats_read()
+        B.soar_search_stats_enable(False)
+        search_stats = dict(c, block_fraction=c["blocks_handed_over"] / max(1, c["blocks"]),
+                            wave_step_fraction=c["wave_steps_with_hand_over"] / max(1, c["wave_steps"]))
 
     # ---- "MSE vs RTN": the plain max-based NVFP4 of Sec. 3.1 on the same tensors
     if args.algorithm in ("rtn", "rtn-amax"):
@@ -423,6 +459,10 @@ def main():
                       if paper else {})},
         "weights_per_s": E / (ms_per_step * 1e-3),
         "hbm_frac_3pass": (BYTES_3PASS * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS) if not rtn_amax else None,
+        "hbm_frac_3pass_note": "algorithmic bytes per weight (three reads of the weights, codes and scales written once) / "
+                               "time / 8 TB/s: a rate of bytes the method has to touch.  Launch groups of at most 256 MiB "
+                               "are found in the last-level cache by the second and third pass, so this is not a DRAM "
+                               "rate for workloads 1-4; workload 5 (470 MB tensors: nothing stays cached) is",
         "hbm_frac_single_touch": BYTES_SEARCH * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "mse_vs_rtn": sse_soar / sse_rtn if sse_rtn > 0 else None,
         "mse_vs_rtn_per_tensor_min_median_max": [ratios[0], ratios[len(ratios) // 2], ratios[-1]] if ratios else None,
@@ -433,6 +473,7 @@ def main():
         "gen_seconds": gen_s,
         "kernels": kernels,
         "roofline": roofline,
+        "search_hand_over": search_stats,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -621,12 +662,9 @@ def bench_mxfp4(args, torch, B, synth, dev):
         t_mx = kernels["mx"]["ms_per_step"] * 1e-3
         if dss:
             ncand = 2 * p.radius + 1
-            flops = (E // 32) * p.n_beta * (32 + 32 + 32 + ncand * 128)      # products, roundings, decoded values, error pairs
-            achieved = flops / t_mx / 1e12
-            roofline = {"kernel": "k_mx", "bound": "alu", "achieved": achieved, "peak": VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": achieved / VALU_PEAK_TFLOPS, "traffic": None,
-                        "flops_per_block_and_factor": 32 + 32 + 32 + ncand * 128,
-                        "note": "all k_mx launches of a step together; HIP-event durations on the launch stream, single-stream pass"}
+            roofline = alu_roofline("k_mx", args.algorithm, args.workload, "bf16", "auto", args.layers,
+                                    (E // 32) * p.n_beta, ncand, t_mx, nelem=32)
+            roofline["note"] = "all k_mx launches of a step together; HIP-event durations on the launch stream, single-stream pass"
         else:
             per_w = 2.0 + 0.5 + 1.0 / 32.0
             gbs = per_w * E / t_mx / 1e9
