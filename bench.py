@@ -314,6 +314,20 @@ def main():
                         "note": "all iteration launches of a step together (launches of tensors that have stopped return "
                                 "at once): one HIP-event bracket per launch group round its T launches, on the launch "
                                 "stream, single-stream pass"}
+            # the same kernel where every launch has work: three iterations, no early stop
+            B.soar_kernel_timing_enable(True)          # drops the events of the pass above
+            p_work = B.soar_arm_params(B.SOAR_METHOD_CJSO_ONLY, iters=3, early_stop_rel=0.0, tiles_per_wg=args.tpw, streams=1)
+            for _ in range(n_prof):
+                B.quantize_batch(descs, p_work, ws)
+            torch.cuda.synchronize()
+            ms_w, n_w = B.soar_kernel_timing_read(B.SOAR_KERNEL_ITER)
+            B.soar_kernel_timing_enable(False)
+            if ms_w > 0:
+                gbs_w = 3 * n_prof * E * per_w / (ms_w * 1e-3) / 1e9
+                roofline["working_launches"] = {
+                    "achieved": gbs_w, "frac": gbs_w / HBM_PEAK_GBS, "iterations": 3, "early_stop": False,
+                    "note": "same tensors, every launch with work (T = 3, no stop): the kernel's own rate; the figure above "
+                            "also carries the launches that find their tensors stopped"}
         else:
             roofline = alu_roofline("k_iter", args.algorithm, args.workload, args.dtype, args.search, args.layers,
                                     block_iters * params.n_beta, ncand, t_iter)
