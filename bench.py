@@ -120,6 +120,8 @@ def parse_args():
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
+    ap.add_argument("--one-launch", choices=["auto", "never"], default="auto",
+                    help="single tensors: let the library take its one-launch kernels (default) or hold it to three passes")
     ap.add_argument("--algorithm", choices=["single-step", "paper", "cjso-only", "dss-only", "rtn", "rtn-amax", "mxfp4", "mxfp4-dss",
                                                "dequantize", "recon-error", "copy-calibration"],
                     default="single-step",
@@ -210,12 +212,14 @@ def main():
     BYTES_3PASS = 3.0 * es + 0.5625
     paper = args.algorithm in ("paper", "cjso-only", "dss-only")      # the iterated path
     rtn_amax = args.algorithm in ("rtn", "rtn-amax")                  # plain NVFP4
+    one_launch = B.SOAR_RESIDENT_AUTO if args.one_launch == "auto" else B.SOAR_RESIDENT_NEVER
     amax_in = [None] * len(specs)
     if rtn_amax:
         if args.algorithm == "rtn-amax":
             # the supplied maxima: measured here, outside the timed region, as a calibration pass would
             amax_in = [w.abs().max().float().reshape(1) for w in weights]
         params = B.soar_default_params(B.SOAR_METHOD_RTN, 0, mode, args.tpw, args.streams)
+        params.resident = one_launch
     elif paper:
         params = iterated_params(B, args, args.streams)
         for o in outs:
@@ -223,6 +227,7 @@ def main():
             o.sse_trace = torch.full((params.iters + 1,), float("nan"), dtype=torch.float64, device=dev)
     else:
         params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
+        params.resident = one_launch
     descs = [B.make_desc(w, o, a) for w, o, a in zip(weights, outs, amax_in)]
     ws = B.new_batch_workspace(descs, params, dev)
 
@@ -339,6 +344,7 @@ def main():
         n_prof = min(args.steps, 5)
         p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,
                                       mode, args.tpw, streams=1)
+        p_one.resident = one_launch
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
             B.quantize_batch(descs, p_one, ws)
