@@ -152,12 +152,14 @@ def parse_args():
                     help="single-step: after the timed region, one more pass with the library's diagnostic counters on: how "
                          "often the certified Eq. 8 search handed a block over to the exhaustive loop")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-widened", action="store_true",
+                    help="default run only: leave out the short timed runs of the other entry points (widened_paths)")
     ap.add_argument("--no-kernel-timing", action="store_true")
     return ap.parse_args()
 
 
-def main():
-    args = parse_args()
+def run(args):
+    """one benchmark as the flags say -> the dict of its JSON line"""
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
@@ -496,7 +498,7 @@ def main():
         "search_hand_over": search_stats,
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out))
+    return out
 
 
 def copy_calibration(torch, dev, gib=1.0, reps=5):
@@ -514,9 +516,9 @@ def copy_calibration(torch, dev, gib=1.0, reps=5):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
-    print(json.dumps({"metric": "copy_calibration", "bytes_read_per_dispatch": n * 4, "bytes_written_per_dispatch": n * 4,
+    return ({"metric": "copy_calibration", "bytes_read_per_dispatch": n * 4, "bytes_written_per_dispatch": n * 4,
                       "dispatches": reps, "ms_per_dispatch": ms, "GBps_read_plus_written": 2 * n * 4 / (ms * 1e-3) / 1e9,
-                      "kernel": "torch vectorized_elementwise_kernel"}))
+                      "kernel": "torch vectorized_elementwise_kernel"})
 
 
 def bench_stored_form(args, torch, B, synth, dev):
@@ -623,7 +625,7 @@ def bench_stored_form(args, torch, B, synth, dev):
         cpu = {"value": es * h.size / dt / 1e9, "unit": f"GB/s {args.dtype} " + ("out" if deq else "in"), "cores": oracle.threads(),
                "kind": "oracle", "seconds": dt, "weights_per_s": h.size / dt,
                "sample": f"tensor {k} ({specs[k].name}, {h.size} weights), {reps} repetitions"}
-    print(json.dumps({
+    return ({
         "metric": "nvfp4_dequantize_throughput" if deq else "nvfp4_recon_error_throughput",
         "value": es * E / (ms_per_step * 1e-3) / 1e9, "unit": f"GB/s {args.dtype} " + ("out" if deq else "in"), "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -633,7 +635,7 @@ def bench_stored_form(args, torch, B, synth, dev):
                    "algorithm": args.algorithm,
                    "stored_form": "single-step SOAR output, resident in HBM"},
         "weights_per_s": E / (ms_per_step * 1e-3), "hbm_frac_of_step": per_w * E / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        **extra, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu}))
+        **extra, "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu})
 
 
 def bench_mxfp4(args, torch, B, synth, dev):
@@ -736,7 +738,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
         cpu = {"value": 2.0 * h.size / dt / 1e9, "unit": "GB/s bf16 in", "cores": oracle.threads(), "kind": "oracle",
                "seconds": dt, "weights_per_s": h.size / dt,
                "sample": f"first {h.shape[0]} rows of the first tensor ({h.size} weights), whole path"}
-    print(json.dumps({
+    return ({
         "metric": "mxfp4_dss_quantize_throughput" if dss else "mxfp4_quantize_throughput",
         "value": 2.0 * E / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s bf16 in", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -750,7 +752,7 @@ def bench_mxfp4(args, torch, B, synth, dev):
         "dequantize": {"entry_point": "soar_mxfp4_dequantize_batch (bf16 out)", "ms_per_step": deq_ms,
                        "hbm_frac": 2.53125 * E / (deq_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "kernels": kernels, "roofline": roofline,
-        "cpu_baseline": cpu}))
+        "cpu_baseline": cpu})
 
 
 def np_or(xs):
@@ -758,6 +760,42 @@ def np_or(xs):
     for x in xs:
         r |= x
     return r
+
+
+# The other entry points on the same workload, a few steps each, so that one default run times every path this
+# build has (whole-job figures, weights resident in HBM; no per-kernel events, no host baseline: the run of
+# each --algorithm by itself reports those).
+WIDENED = (("paper", 2, 1), ("cjso-only", 3, 1), ("dss-only", 2, 1), ("rtn-amax", 10, 2), ("mxfp4-dss", 2, 1),
+           ("dequantize", 10, 2), ("recon-error", 10, 2))
+
+
+def widened_paths(args):
+    import torch
+    rows = {}
+    for alg, steps, warmup in WIDENED:
+        a = argparse.Namespace(**vars(args))
+        a.algorithm, a.steps, a.warmup = alg, steps, warmup
+        a.no_cpu_baseline = a.no_kernel_timing = True
+        a.reps, a.search_stats, a.graph, a.cold = 0, False, False, False
+        d = run(a)
+        rows[alg] = {k: d.get(k) for k in ("metric", "value", "unit", "ms_per_step", "steps", "warmup", "weights_per_s")}
+        for k in ("mse_vs_rtn", "mse_vs_plain_mxfp4"):
+            if d.get(k) is not None:
+                rows[alg][k] = d[k]
+        if d.get("config", {}).get("iterations_run_min_mean_max"):
+            rows[alg]["iterations_run_min_mean_max"] = d["config"]["iterations_run_min_mean_max"]
+        torch.cuda.empty_cache()
+    return rows
+
+
+def main():
+    args = parse_args()
+    out = run(args)
+    headline = (args.algorithm == "single-step" and args.workload == 4 and not args.layers and args.dtype == "bf16"
+                and not args.graph)
+    if headline and not args.no_widened:
+        out["widened_paths"] = widened_paths(args)
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":
