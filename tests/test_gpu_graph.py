@@ -154,3 +154,67 @@ def test_two_callers_on_two_streams_share_the_internal_stream():
             again = B.mx_quantize(w, B.soar_mx_default_params(n_beta=5))
             torch.cuda.synchronize()
             assert torch.equal(m.codes, again.codes) and torch.equal(m.scales, again.scales)
+
+
+def test_host_threads_call_the_library_at_once():
+    """Four host threads, each with its own stream, workspace and outputs, call the batch entry point (two
+    launch groups: the shared internal stream and its events), the single-tensor entry point (the one-launch
+    kernel, or the three-pass path when another thread's may still run), the MXFP4 one and the stored-form
+    ones at the same time, several rounds.  The foreign calls run without the interpreter lock.  Every result
+    equals the one computed alone."""
+    import threading
+    specs = synth.workload_specs(4, 8)
+    p = B.soar_default_params(B.SOAR_METHOD_SOAR, 4)
+    mp = B.soar_mx_default_params(n_beta=5)
+    jobs = []
+    for k in range(4):
+        ws = [synth.make_weight(s, DEV) for s in specs[7 * k: 7 * k + 14]]
+        one = synth.make_weight(specs[7 * k], DEV)
+        jobs.append((ws, one))
+    refs = []
+    for ws, one in jobs:
+        refs.append((B.quantize_tensors(ws, p), B.quantize(one), B.mx_quantize(one, mp)))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in jobs]
+    results, errors = [None] * len(jobs), []
+    start = threading.Barrier(len(jobs))
+
+    def work(k):
+        try:
+            torch.cuda.set_device(0)
+            ws, one = jobs[k]
+            got = []
+            start.wait()
+            with torch.cuda.stream(streams[k]):
+                for rep in range(5):
+                    batch = B.quantize_tensors(ws, p)
+                    single = B.quantize(one)
+                    mx = B.mx_quantize(one, mp)
+                    back = B.dequantize(single)
+                    errs = B.recon_error_batch(ws, batch)
+                    got.append((batch, single, mx, back, errs))
+            streams[k].synchronize()
+            results[k] = got
+        except Exception as e:                       # noqa: BLE001 -- reported by the main thread
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a thread did not finish"
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for k, (ref_batch, ref_single, ref_mx) in enumerate(refs):
+        for batch, single, mx, back, errs in results[k]:
+            for a, r in zip(batch, ref_batch):
+                _same(a, r)
+            # one launch or three passes, whichever the guard chose: same bytes, the error sum in another order
+            assert torch.equal(single.codes, ref_single.codes) and torch.equal(single.scales, ref_single.scales)
+            assert single.global_scale.item() == ref_single.global_scale.item()
+            assert abs(single.sse.item() - ref_single.sse.item()) <= 1e-12 * ref_single.sse.item()
+            assert torch.equal(mx.codes, ref_mx.codes) and torch.equal(mx.scales, ref_mx.scales)
+            assert torch.equal(back, B.dequantize(ref_single))
+            for j, r in enumerate(ref_batch):
+                assert abs(errs[j].item() - r.sse.item()) <= 1e-9 * max(r.sse.item(), 1e-300)
