@@ -438,7 +438,8 @@ soar_status soar_rcp_midrange_f32(const float *d_x, int64_t n, float *d_out, voi
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every kernel the library
- * launches is bracketed by HIP events on its stream.  soar_kernel_timing_read
+ * launches is bracketed by HIP events on its stream (events without the
+ * system-scope fence: they measure and order nothing).  soar_kernel_timing_read
  * synchronises, returns total milliseconds and launch count of one kernel
  * family since the last reset, and soar_kernel_timing_enable(…) resets.
  * (SOAR_KERNEL_ITER: one bracket round all iteration launches of a launch group,

@@ -192,7 +192,10 @@ struct ScopedTimer {
     ScopedTimer(int id_, hipStream_t st_) : id(id_), st(st_)
     {
         if (!g_timing.enabled || t_no_event_timing) return;
-        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { e0 = e1 = nullptr; return; }
+        // timing only: no system-scope fence (cache write-back and invalidation) with the record, which would be
+        // charged to the kernel between the two events and to the one after
+        if (hipEventCreateWithFlags(&e0, hipEventDisableSystemFence) != hipSuccess ||
+            hipEventCreateWithFlags(&e1, hipEventDisableSystemFence) != hipSuccess) { e0 = e1 = nullptr; return; }
         (void)hipEventRecord(e0, st);
     }
     ~ScopedTimer()
