@@ -267,3 +267,39 @@ def test_arrival_counting_names_exactly_one_last_workgroup():
             assert last == [order[-1]], (G, last)
             assert slots == [next(iter(share[k])) for k in range(ns)] and top == ns
     assert B.soar_debug_arrival_plan(0, 0) == (0xFFFFFFFF,) * 3 and B.soar_debug_arrival_plan(5, 5) == (0xFFFFFFFF,) * 3
+
+
+def test_counter_table_that_bench_quotes_is_well_formed_and_points_at_committed_summaries():
+    """bench.py takes roofline.traffic and the executed-instruction counts from profiles/pmc_table.json: every
+    entry names a committed summary under profiles/, carries either both byte figures or an instruction count,
+    and the lookup finds the headline kernel's entry (and says why when there is none)."""
+    import importlib.util
+    import json
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    with open(bench.PMC_TABLE) as f:
+        table = json.load(f)
+    assert table["calibration"]["fetch_scale"] > 0 and table["calibration"]["write_scale"] > 0
+    keys = set()
+    for e in table["entries"]:
+        assert os.path.isfile(os.path.join(ROOT, e["source"])) and e["source"].startswith("profiles/"), e
+        assert e["dtype"] in ("bf16", "fp32") and e["workload"].startswith("config") and e["kernel"].startswith("k_"), e
+        has_bytes = "read_B_per_weight" in e and "written_B_per_weight" in e
+        has_insts = "valu_lane_insts_per_block_factor" in e
+        assert has_bytes != has_insts, e
+        if has_bytes:
+            assert 0 <= e["written_B_per_weight"] < 8 and 0 < e["read_B_per_weight"] < 16, e
+        else:
+            assert 10 < e["valu_lane_insts_per_block_factor"] < 1000, e
+        key = (e["algorithm"], e["workload"], e["dtype"], e["kernel"], e.get("search", "auto"))
+        assert key not in keys, key
+        keys.add(key)
+    e, why = bench.pmc_entry("single-step", 4, "bf16", "k_search")
+    assert e is not None and why == e["source"]
+    traffic, _ = bench.traffic_per_launch("single-step", 4, "bf16", "k_search", 1e6)
+    assert traffic == pytest.approx((e["read_B_per_weight"] + e["written_B_per_weight"]) * 1e6)
+    none, why = bench.pmc_entry("single-step", 4, "bf16", "k_search", layers=2)
+    assert none is None and "subset" in why
+    none, why = bench.traffic_per_launch("single-step", 9, "bf16", "k_nothing", 1.0)
+    assert none is None and "no counter run" in why
