@@ -466,52 +466,62 @@ __device__ __forceinline__ void reset_counters(uint32_t *slots, uint32_t *top)
     if (threadIdx.x == 0) *top = 0u;
 }
 
-// Adjacent-pair tree over the per-workgroup partial sums part[0..P), zero-padded
-// to a power of two.  All lanes of the workgroup must call; the result is valid
-// in lane 0.  Chunks of 8*kWG partials are folded (8 per lane in registers, then
-// LDS) and combined with a binary-counter stack.
-__device__ double tree_of_partials(const double *part, uint32_t P, double *lds /* kWG */, double *stack /* 16 */)
+// Adjacent-pair trees over NV arrays of per-workgroup partial sums (array n starts at part + n * kMaxPartials,
+// entries 0..P), zero-padded to a power of two.  All kWG lanes of the workgroup must call; result[] is valid in
+// lane 0.  Chunks of 8*kWG (4*kWG for three arrays) partials: that many adjacent ones per lane in registers, the DPP tree over a wave's lanes,
+// the four wave sums through LDS (lds: 4 NV doubles), and a binary-counter stack over the chunks (stack: 32
+// doubles per array).  The loads of all arrays are issued together: the last workgroup pays one trip to
+// memory and two barriers per chunk, whatever NV.
+template <int NV>
+__device__ void trees_of_partials(const double *part, uint32_t P, double *lds, double *stack, double result[NV])
 {
-    constexpr uint32_t kPerLane = 8;
+    constexpr uint32_t kPerLane = NV >= 3 ? 4 : 8;       // adjacent partials per lane and array: 24 to 32 registers
+    static_assert(kWG == 256, "four wave sums per chunk");
     uint32_t P2 = 1;
     while (P2 < P) P2 <<= 1;
     const uint32_t C = P2 > (uint32_t)kWG ? (P2 / kWG < kPerLane ? P2 / kWG : kPerLane) : 1;
     const uint32_t chunk = C * kWG;
     const uint32_t nchunks = P2 > chunk ? P2 / chunk : 1;
-    const uint32_t tid = threadIdx.x;
-    double result = 0.0;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+#pragma unroll
+    for (int n = 0; n < NV; ++n) result[n] = 0.0;
     for (uint32_t ch = 0; ch < nchunks; ++ch) {
-        double v[kPerLane];
+        double v[NV][kPerLane];
 #pragma unroll
-        for (uint32_t k = 0; k < kPerLane; ++k) {
-            const uint32_t idx = ch * chunk + tid * C + k;
-            v[k] = (k < C && idx < P)
-                       ? __hip_atomic_load(part + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                       : 0.0;
+        for (int n = 0; n < NV; ++n)
+#pragma unroll
+            for (uint32_t k = 0; k < kPerLane; ++k) {
+                const uint32_t idx = ch * chunk + tid * C + k;
+                v[n][k] = (k < C && idx < P)
+                              ? __hip_atomic_load(part + (size_t)n * kMaxPartials + idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : 0.0;
+            }
+        double w[NV];
+#pragma unroll
+        for (int n = 0; n < NV; ++n) {
+#pragma unroll
+            for (uint32_t s = 1; s < kPerLane; s <<= 1)
+#pragma unroll
+                for (uint32_t k = 0; k < kPerLane; k += 2 * s) v[n][k] = v[n][k] + v[n][k + s];
+            w[n] = wave_pair_tree(v[n][0]);
         }
+        __syncthreads();          // lds may alias what the caller used before; lane 0 has read the chunk before
+        if (lane == 0) {
 #pragma unroll
-        for (uint32_t s = 1; s < kPerLane; s <<= 1)
-#pragma unroll
-            for (uint32_t k = 0; k < kPerLane; k += 2 * s) v[k] = v[k] + v[k + s];
-        __syncthreads();
-        lds[tid] = v[0];
-        __syncthreads();
-        for (uint32_t n = kWG; n > 1; n >>= 1) {
-            double t = 0.0;
-            if (tid < n / 2) t = lds[2 * tid] + lds[2 * tid + 1];
-            __syncthreads();
-            if (tid < n / 2) lds[tid] = t;
-            __syncthreads();
+            for (int n = 0; n < NV; ++n) lds[n * 4 + wave] = w[n];
         }
+        __syncthreads();
         if (tid == 0) {
-            double x = lds[0];
-            uint32_t lvl = 0;
-            while ((ch >> lvl) & 1u) { x = stack[lvl] + x; ++lvl; }
-            stack[lvl] = x;
-            result = x;
+#pragma unroll
+            for (int n = 0; n < NV; ++n) {
+                double x = (lds[n * 4] + lds[n * 4 + 1]) + (lds[n * 4 + 2] + lds[n * 4 + 3]);
+                uint32_t lvl = 0;
+                while ((ch >> lvl) & 1u) { x = stack[n * 32 + lvl] + x; ++lvl; }
+                stack[n * 32 + lvl] = x;
+                result[n] = x;
+            }
         }
     }
-    return result;
 }
 
 // which tensor of the launch this workgroup works on, and its index there

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
     __shared__ double s_wave[3][4];
     __shared__ double s_stack[3][32];
     __shared__ uint32_t s_last;
-    double *s_tree = reinterpret_cast<double *>(s_blocks);      // tree_of_partials, after the last group: kWG doubles
+    double *s_tree = reinterpret_cast<double *>(s_blocks);      // trees_of_partials, after the last group
     static_assert(sizeof(float4) * kStage >= sizeof(double), "s_tree fits s_blocks");
 
     uint32_t lwg;
@@ -335,9 +335,9 @@ __global__ __launch_bounds__(kWG) void k_iter_init(const Batch batch)
     }
     __syncthreads();
     if (!s_last) return;
-    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
-    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
-    const double E = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    double NME[3];
+    trees_of_partials<3>(t.part, t.n_wg, s_tree, &s_stack[0][0], NME);
+    const double N = NME[0], M = NME[1], E = NME[2];
     if (tid == 0) {
         t.ctrl->alpha0 = alpha0;
         // the global scale of iteration 0: Eq. 5, or unchanged when the closed-form stage is left out
@@ -486,9 +486,9 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     }
     __syncthreads();
     if (!s_last) return;
-    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
-    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
-    const double cur = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    double NME[3];
+    trees_of_partials<3>(t.part, t.n_wg, s_tree, &s_stack[0][0], NME);
+    const double N = NME[0], M = NME[1], cur = NME[2];
     if (tid == 0) finish_iteration(batch, t, N, M, cur, alpha, degenerate, allzero, dss_only);
     reset_counters(counters, &t.ctrl->top[2]);
 }
@@ -499,14 +499,15 @@ __global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 // by memory (weights and ratio read, ratio, codes and scale written), so it is built like k_stats: several
 // consecutive tiles per workgroup, the three sums through the staged tree, streaming stores for the outputs
 // (the weights and the ratio are read again by the next iteration and stay in the last-level cache).
+// (held to 64 registers: eight waves per SIMD hide the loads of this memory-bound kernel)
 template <int DT>
-__global__ __launch_bounds__(kWG) void k_cjso(const Batch batch)
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(8))) void k_cjso(const Batch batch)
 {
     __shared__ float4 s_blocks[kStage * kWG];
     __shared__ double s_wave[3][4];
     __shared__ double s_stack[3][32];
     __shared__ uint32_t s_last;
-    double *s_tree = reinterpret_cast<double *>(s_blocks);      // tree_of_partials, after the last group: kWG doubles
+    double *s_tree = reinterpret_cast<double *>(s_blocks);      // trees_of_partials, after the last group
 
     uint32_t lwg;
     const Task t = batch.t[find_task(batch, lwg)];
@@ -564,9 +565,9 @@ __global__ __launch_bounds__(kWG) void k_cjso(const Batch batch)
     }
     __syncthreads();
     if (!s_last) return;
-    const double N = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
-    const double M = tree_of_partials(t.part + kMaxPartials, t.n_wg, s_tree, s_stack[1]);
-    const double cur = tree_of_partials(t.part + 2 * kMaxPartials, t.n_wg, s_tree, s_stack[2]);
+    double NME[3];
+    trees_of_partials<3>(t.part, t.n_wg, s_tree, &s_stack[0][0], NME);
+    const double N = NME[0], M = NME[1], cur = NME[2];
     if (tid == 0) finish_iteration(batch, t, N, M, cur, alpha, degenerate, allzero, false);
     reset_counters(counters, &t.ctrl->top[2]);
 }

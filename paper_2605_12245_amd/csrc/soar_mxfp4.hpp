@@ -321,7 +321,8 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
     if (tid == 0) s_last = arrive_is_last(counters, &t.ctrl->top[0], t.n_wg, lwg) ? 1u : 0u;
     __syncthreads();
     if (!s_last) return;
-    const double total = tree_of_partials(t.part, t.n_wg, s_tree, s_stack[0]);
+    double total;
+    trees_of_partials<1>(t.part, t.n_wg, s_tree, &s_stack[0][0], &total);
     if (tid == 0) {
         const uint32_t flag = __hip_atomic_load(&t.ctrl->amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (t.sse) *t.sse = total;

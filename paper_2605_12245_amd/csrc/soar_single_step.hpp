@@ -185,8 +185,9 @@ __global__ __launch_bounds__(kWG) void k_stats(const Batch batch)
     __syncthreads();
     if (!s_last) return;
     // last workgroup of the tensor: finish the trees and apply Eq. 5
-    const double N = tree_of_partials(partN, t.n_wg, s_tree, s_stack[0]);
-    const double M = tree_of_partials(partM, t.n_wg, s_tree, s_stack[1]);
+    double NM[2];
+    trees_of_partials<2>(t.part, t.n_wg, s_tree, &s_stack[0][0], NM);
+    const double N = NM[0], M = NM[1];
     if (tid == 0) {
         float alpha1 = (M > 0.0) ? (float)(N / M) : alpha0;
         if (amax_bits == 0u) alpha1 = 1.0f;
@@ -408,7 +409,8 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     }
     __syncthreads();
     if (!s_last) return;
-    const double total = tree_of_partials(partS, t.n_wg, s_tree, s_stack);
+    double total;
+    trees_of_partials<1>(partS, t.n_wg, s_tree, s_stack, &total);
     if (tid == 0) {
         if (t.sse) *t.sse = total;
         if (t.status)
