@@ -119,6 +119,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="workloads 4/5: first N layers only (0 = all)")
     ap.add_argument("--search", choices=["auto", "full"], default="auto")
     ap.add_argument("--tpw", type=int, default=0, help="force tiles per workgroup (0 = library default)")
+    ap.add_argument("--tpw-absmax", type=int, default=0, help="single-step / rtn: force the maximum pass alone (0 = as --tpw)")
+    ap.add_argument("--tpw-search", type=int, default=0, help="single-step / rtn: force the search pass alone (0 = as --tpw)")
     ap.add_argument("--streams", type=int, default=0, help="0 = library default, 1 = caller's stream only")
     ap.add_argument("--one-launch", choices=["auto", "never"], default="auto",
                     help="single tensors: let the library take its one-launch kernels (default) or hold it to three passes")
@@ -222,6 +224,7 @@ def run(args):
             amax_in = [w.abs().max().float().reshape(1) for w in weights]
         params = B.soar_default_params(B.SOAR_METHOD_RTN, 0, mode, args.tpw, args.streams)
         params.resident = one_launch
+        params.tiles_per_wg_absmax, params.tiles_per_wg_search = args.tpw_absmax, args.tpw_search
     elif paper:
         params = iterated_params(B, args, args.streams)
         for o in outs:
@@ -230,6 +233,7 @@ def run(args):
     else:
         params = B.soar_default_params(B.SOAR_METHOD_SOAR, K, mode, args.tpw, args.streams)
         params.resident = one_launch
+        params.tiles_per_wg_absmax, params.tiles_per_wg_search = args.tpw_absmax, args.tpw_search
     descs = [B.make_desc(w, o, a) for w, o, a in zip(weights, outs, amax_in)]
     ws = B.new_batch_workspace(descs, params, dev)
 
@@ -347,6 +351,7 @@ def run(args):
         p_one = B.soar_default_params(B.SOAR_METHOD_RTN if rtn_amax else B.SOAR_METHOD_SOAR, 0 if rtn_amax else K,
                                       mode, args.tpw, streams=1)
         p_one.resident = one_launch
+        p_one.tiles_per_wg_absmax, p_one.tiles_per_wg_search = args.tpw_absmax, args.tpw_search
         B.soar_kernel_timing_enable(True)
         for _ in range(n_prof):
             B.quantize_batch(descs, p_one, ws)

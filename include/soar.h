@@ -144,6 +144,12 @@ typedef struct {
     int32_t  resident_wait_us; /* 0 = library default (2 s); > 0: the bound, in microseconds,
                                 after which a workgroup of that kernel stops waiting, sets
                                 SOAR_STATUS_GAVE_UP and leaves (every workgroup then does)   */
+    int32_t  tiles_per_wg_absmax; /* single-step path: the maximum pass and the search pass   */
+    int32_t  tiles_per_wg_search; /* have launch shapes of their own (the library picks them by
+                                the schedule: kernels of two launch groups share the GPU in a
+                                batch of several groups).  0 = as tiles_per_wg says, else the
+                                library's choice; a power of two <= 65536 forces that pass
+                                (tests and tuning: outputs must not depend on it)           */
 } soar_params;
 
 /* Fills *p with the single-step defaults: SOAR, block 16, T = 1, K = 4, beta = {1},

@@ -59,6 +59,7 @@ class soar_params(C.Structure):
         ("beta_lo", C.c_float), ("beta_hi", C.c_float), ("early_stop_rel", C.c_float),
         ("search_mode", C.c_int32), ("tiles_per_wg", C.c_int32), ("streams", C.c_int32),
         ("dd_mode", C.c_int32), ("resident", C.c_int32), ("resident_wait_us", C.c_int32),
+        ("tiles_per_wg_absmax", C.c_int32), ("tiles_per_wg_search", C.c_int32),
     ]
 
 

@@ -47,6 +47,12 @@ constexpr size_t kPartialsBytes = 3 * sizeof(double) * (size_t)kMaxPartials;
 constexpr size_t kSlotBytes = kZeroedBytes + kPartialsBytes;                   // per tensor slot
 static_assert(kSlotBytes % 256 == 0, "slot size");
 
+// How one pass walks a tensor: workgroups wg_begin .. wg_begin + n_wg - 1 of the grid, tiles_per_wg (a power of
+// two) tiles of kWG blocks each.
+struct Shape {
+    uint32_t tiles_per_wg, n_wg, wg_begin;
+};
+
 // One tensor of a launch.
 struct Task {
     const void *w;
@@ -68,6 +74,7 @@ struct Task {
     double   *part;          // [3][kMaxPartials] partial sums N, M, error
     float    *rho;           // [nblk] a / b of the current state, or -Delta^d where b == 0
     const float *amax_in;    // supplied maximum (plain NVFP4 only), or null: measured by k_absmax
+    Shape    absmax, search; // shapes of k_absmax and k_search (tiles_per_wg, wg_begin, n_wg above: every other kernel)
     int32_t  *iters_run;     // iterated path, may be null
     double   *trace;         // iterated path, may be null: iters+1 errors
 };
@@ -532,6 +539,17 @@ __device__ __forceinline__ uint32_t find_task(const Batch &b, uint32_t &lwg)
     for (uint32_t j = 1; j < b.n; ++j)
         if (id >= b.t[j].wg_begin) k = j;
     lwg = id - b.t[k].wg_begin;
+    return k;
+}
+
+// the same for a pass with a shape of its own
+__device__ __forceinline__ uint32_t find_task(const Batch &b, Shape Task::*which, uint32_t &lwg)
+{
+    const uint32_t id = blockIdx.x;
+    uint32_t k = 0;
+    for (uint32_t j = 1; j < b.n; ++j)
+        if (id >= (b.t[j].*which).wg_begin) k = j;
+    lwg = id - (b.t[k].*which).wg_begin;
     return k;
 }
 

@@ -224,7 +224,8 @@ bool valid_params(const soar_params *p)
     if (p->method == SOAR_METHOD_DSS_ONLY && p->dd_mode != SOAR_DD_WINDOW) return false;
     if (p->dss_radius < 0 || p->dss_radius > 125) return false;
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
-    if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    for (int32_t v : {p->tiles_per_wg, p->tiles_per_wg_absmax, p->tiles_per_wg_search})
+        if (v < 0 || v > 65536 || (v & (v - 1))) return false;
     if (p->streams < 0 || p->streams > kLanes) return false;
     if (p->resident != SOAR_RESIDENT_AUTO && p->resident != SOAR_RESIDENT_NEVER) return false;
     if (p->resident_wait_us < 0) return false;
@@ -263,8 +264,24 @@ size_t per_block_bytes(int64_t rows, int64_t cols)
     return align256(nblk * sizeof(float));
 }
 
-// addressing and launch shape of one tensor; the workspace fields stay unset
-Task make_task(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t forced_tpw)
+// Tiles per workgroup the three passes of the single-step path ask for.  A call of one launch group runs its
+// kernels one after the other, and four tiles suit each of them best.  A call of several groups has kernels of
+// two groups on the machine at once (see SecondLane), and how their workgroups share the compute units decides
+// the step: with 8 tiles per workgroup in the statistics pass and 16 in the search the full-model workload
+// takes 7.26 ms instead of 8.08 (swept over 1..4 x 4..32 x 8..32: profiles/config4_launch_shape_sweep.md),
+// although the search alone is 5 % slower that way; plain NVFP4 (two passes) likes 8 in its search.
+struct WantedShapes { uint32_t absmax, stats, search; };
+WantedShapes wanted_shapes(bool several_groups, int method, bool iterated, bool one_pass, int64_t bytes)
+{
+    if (!several_groups || iterated || one_pass) return {(uint32_t)kStage, (uint32_t)kStage, (uint32_t)kStage};
+    // a tensor that is a launch group by itself and larger than the last-level cache streams from HBM in every
+    // pass; plain NVFP4 has two passes only
+    if (method == SOAR_METHOD_RTN || bytes > kGroupByteCap) return {(uint32_t)kStage, (uint32_t)kStage, 8u};
+    return {(uint32_t)kStage, 8u, 16u};
+}
+
+// addressing and launch shapes of one tensor; the workspace fields and the first workgroups stay unset
+Task make_task(const void *w, int64_t rows, int64_t cols, int64_t ld, const WantedShapes &forced, const WantedShapes &want)
 {
     Task t;
     std::memset(&t, 0, sizeof(t));
@@ -274,12 +291,22 @@ Task make_task(const void *w, int64_t rows, int64_t cols, int64_t ld, uint32_t f
     t.nblk = (uint32_t)(rows * (cols / 16));
     t.contiguous = (ld == cols) ? 1u : 0u;
     const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
-    uint32_t tpw = 1;
-    while (tpw < (uint32_t)kStage && tpw * 2 <= tiles) tpw <<= 1;
-    if (forced_tpw) tpw = forced_tpw;
-    while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
-    t.tiles_per_wg = tpw;
-    t.n_wg = (tiles + tpw - 1) / tpw;
+    auto shape = [&](uint32_t wanted, uint32_t forced_tpw) {
+        Shape sh;
+        uint32_t tpw = 1;
+        while (tpw < wanted && tpw * 2 <= tiles) tpw <<= 1;
+        if (forced_tpw) tpw = forced_tpw;
+        while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;
+        sh.tiles_per_wg = tpw;
+        sh.n_wg = (tiles + tpw - 1) / tpw;
+        sh.wg_begin = 0;
+        return sh;
+    };
+    const Shape base = shape(want.stats, forced.stats);
+    t.tiles_per_wg = base.tiles_per_wg;
+    t.n_wg = base.n_wg;
+    t.absmax = shape(want.absmax, forced.absmax);
+    t.search = shape(want.search, forced.search);
     return t;
 }
 
@@ -392,26 +419,27 @@ SecondLane *second_lane()
     return lanes[dev].usable ? &lanes[dev] : nullptr;
 }
 
+// grids: every pass has its own number of workgroups (Task::absmax, the base shape, Task::search)
 template <int DT>
-soar_status launch_group(const Batch &b, uint32_t total_wg, int method, hipStream_t st)
+soar_status launch_group(const Batch &b, uint32_t wg_absmax, uint32_t wg_stats, uint32_t wg_search, int method, hipStream_t st)
 {
     if (b.t[0].amax_in == nullptr) {       // all tensors of a batch supply their maximum, or none does
         ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
-        hipLaunchKernelGGL(k_absmax<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        hipLaunchKernelGGL(k_absmax<DT>, dim3(wg_absmax), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     }
     if (method == SOAR_METHOD_SOAR) {
         {
             ScopedTimer t(SOAR_KERNEL_STATS, st);
-            hipLaunchKernelGGL(k_stats<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+            hipLaunchKernelGGL(k_stats<DT>, dim3(wg_stats), dim3(kWG), 0, st, b);
             SOAR_LAUNCH_CHECK();
         }
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(total_wg), dim3(kWG), 0, st, b);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_SOAR>), dim3(wg_search), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     } else {
         ScopedTimer t(SOAR_KERNEL_SEARCH, st);
-        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(total_wg), dim3(kWG), 0, st, b);
+        hipLaunchKernelGGL((k_search<DT, SOAR_METHOD_RTN>), dim3(wg_search), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     }
     return SOAR_OK;
@@ -428,11 +456,11 @@ size_t iter_lds_bytes(const Batch &b)
 // absmax, the Eq. 1-2 state, then one launch per iteration; a tensor that has
 // stopped early (or is degenerate) makes its workgroups of the later launches return at once
 template <int DT>
-soar_status launch_group_iter(Batch &b, uint32_t total_wg, int iters, hipStream_t st)
+soar_status launch_group_iter(Batch &b, uint32_t wg_absmax, uint32_t total_wg, int iters, hipStream_t st)
 {
     {
         ScopedTimer t(SOAR_KERNEL_ABSMAX, st);
-        hipLaunchKernelGGL(k_absmax<DT>, dim3(total_wg), dim3(kWG), 0, st, b);
+        hipLaunchKernelGGL(k_absmax<DT>, dim3(wg_absmax), dim3(kWG), 0, st, b);
         SOAR_LAUNCH_CHECK();
     }
     {
@@ -478,11 +506,12 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
     // one tensor, single-step settings, default launch shape: the whole path in one launch that keeps the
     // tensor in registers, if its grid fits the GPU (see k_resident); only the slot's flag words are used
     ResidentPlan plan;
-    if (n == 1 && !iterated && !descs[0].d_amax_in && params->tiles_per_wg == 0 && params->resident == SOAR_RESIDENT_AUTO &&
+    if (n == 1 && !iterated && !descs[0].d_amax_in && params->tiles_per_wg == 0 && params->tiles_per_wg_absmax == 0 &&
+        params->tiles_per_wg_search == 0 && params->resident == SOAR_RESIDENT_AUTO &&
         resident_plan(descs[0].rows * (descs[0].cols / 16), device_facts().compute_units, plan) &&
         (plan.G == 1 || resident_may_start(st))) {
         const soar_tensor_desc &d = descs[0];
-        Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, 0);
+        Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, WantedShapes{0u, 0u, 0u}, wanted_shapes(false, params->method, false, false, 0));
         t.codes = d.d_codes;
         t.scales = d.d_scales;
         t.gscale = d.d_global_scale;
@@ -554,11 +583,14 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         // (the closed-form arm has no search and streams like the single-step kernels)
         const bool searching = iterated && params->method != SOAR_METHOD_CJSO_ONLY;
         const uint32_t tpw = params->tiles_per_wg ? (uint32_t)params->tiles_per_wg : (searching ? 1u : 0u);
-        uint32_t wg = 0;
+        uint32_t wg = 0, wg_absmax = 0, wg_search = 0;
         char *per_block = lane_base + (size_t)kGroupMax * kSlotBytes;
         for (int32_t k = i; k < j; ++k) {
             const soar_tensor_desc &d = descs[k];
-            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, tpw);
+            const WantedShapes forced = {params->tiles_per_wg_absmax ? (uint32_t)params->tiles_per_wg_absmax : tpw, tpw,
+                                         params->tiles_per_wg_search ? (uint32_t)params->tiles_per_wg_search : tpw};
+            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, forced,
+                               wanted_shapes(n_groups > 1, params->method, iterated, d.d_amax_in != nullptr, weight_bytes(d)));
             t.iters_run = d.d_iters_run;
             t.trace = d.d_sse_trace;
             t.amax_in = d.d_amax_in;
@@ -569,6 +601,10 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             t.status = d.d_status;
             t.wg_begin = wg;
             wg += t.n_wg;
+            t.absmax.wg_begin = wg_absmax;
+            wg_absmax += t.absmax.n_wg;
+            t.search.wg_begin = wg_search;
+            wg_search += t.search.n_wg;
             char *slot = lane_base + (size_t)(k - i) * kSlotBytes;
             t.ctrl = reinterpret_cast<Ctrl *>(slot);
             t.counters = reinterpret_cast<uint32_t *>(slot + kCtrlBytes);
@@ -579,11 +615,12 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
             b.t[k - i] = t;
         }
         if (iterated)
-            result = descs[i].dtype == SOAR_BF16 ? launch_group_iter<SOAR_BF16>(b, wg, params->iters, lane_stream[lane])
-                                                 : launch_group_iter<SOAR_FP32>(b, wg, params->iters, lane_stream[lane]);
+            result = descs[i].dtype == SOAR_BF16 ? launch_group_iter<SOAR_BF16>(b, wg_absmax, wg, params->iters, lane_stream[lane])
+                                                 : launch_group_iter<SOAR_FP32>(b, wg_absmax, wg, params->iters, lane_stream[lane]);
         else
-            result = descs[i].dtype == SOAR_BF16 ? launch_group<SOAR_BF16>(b, wg, params->method, lane_stream[lane])
-                                                 : launch_group<SOAR_FP32>(b, wg, params->method, lane_stream[lane]);
+            result = descs[i].dtype == SOAR_BF16
+                         ? launch_group<SOAR_BF16>(b, wg_absmax, wg, wg_search, params->method, lane_stream[lane])
+                         : launch_group<SOAR_FP32>(b, wg_absmax, wg, wg_search, params->method, lane_stream[lane]);
         i = j;
     }
     // always join, also after a failed launch, so that the caller's stream stays ordered
@@ -712,6 +749,8 @@ void soar_default_params(soar_params *p)
     p->dd_mode = SOAR_DD_WINDOW;
     p->resident = SOAR_RESIDENT_AUTO;
     p->resident_wait_us = 0;
+    p->tiles_per_wg_absmax = 0;
+    p->tiles_per_wg_search = 0;
 }
 
 void soar_paper_params(soar_params *p)

@@ -50,15 +50,16 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
     __shared__ uint32_t s_wave[4];
     __shared__ uint32_t s_last;
     uint32_t lwg;
-    const Task t = batch.t[find_task(batch, lwg)];
+    const Task t = batch.t[find_task(batch, &Task::absmax, lwg)];
+    const Shape sh = t.absmax;
     const uint32_t tid = threadIdx.x;
     constexpr int kChunks = DT == SOAR_BF16 ? 2 : 4;      // 16-byte pieces per block
 
     // tiles are dealt round-robin over the tensor's workgroups, so that at any moment
     // the workgroups in flight sweep one contiguous window of memory
     uint32_t m = 0;
-    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
-        const uint32_t i = (k * t.n_wg + lwg) * kWG + tid;
+    for (uint32_t k = 0; k < sh.tiles_per_wg; ++k) {
+        const uint32_t i = (k * sh.n_wg + lwg) * kWG + tid;
         if (i >= t.nblk) break;
         const size_t off = block_offset(t, i) * (DT == SOAR_BF16 ? 2 : 4);
         const char *p = static_cast<const char *>(t.w) + off;
@@ -75,10 +76,10 @@ __global__ __launch_bounds__(kWG) void k_absmax(const Batch batch)
     uint32_t *counters = t.counters;                       // kernel 0
     if (tid == 0) {
         m = max(max(s_wave[0], s_wave[1]), max(s_wave[2], s_wave[3]));
-        const uint32_t ns = t.n_wg < (uint32_t)kSlots ? t.n_wg : (uint32_t)kSlots;
+        const uint32_t ns = sh.n_wg < (uint32_t)kSlots ? sh.n_wg : (uint32_t)kSlots;
         // arrive_is_last waits for this read-modify-write to complete before it counts the workgroup in
         __hip_atomic_fetch_max(t.slot_max + (lwg % ns) * kSlotStride, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = arrive_is_last(counters, &t.ctrl->top[0], t.n_wg, lwg) ? 1u : 0u;
+        s_last = arrive_is_last(counters, &t.ctrl->top[0], sh.n_wg, lwg) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
@@ -306,8 +307,10 @@ __device__ __forceinline__ void count_search(unsigned long long *stats, bool cer
 
 // Eq. 6, projection, new assignment, Eq. 8 search, packing, error sum.
 // METHOD RTN emits the Eq. 1-2 state instead.
+// (bf16: held to 64 registers, eight waves per SIMD; left to itself the compiler takes 83 for a shorter schedule and loses more in
+// occupancy than it gains)
 template <int DT, int METHOD>
-__global__ __launch_bounds__(kWG) void k_search(const Batch batch)
+__global__ __launch_bounds__(kWG) __attribute__((amdgpu_waves_per_eu(DT == SOAR_BF16 ? 8 : 4))) void k_search(const Batch batch)
 {
     __shared__ double s_wave[4];
     __shared__ double s_tree[kWG];
@@ -320,7 +323,8 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     __shared__ u32x4 s_x[kExchange ? kWG * kP : 1];    // load_wave_blocks: one region per wave
 
     uint32_t lwg;
-    const Task t = batch.t[find_task(batch, lwg)];
+    const Task t = batch.t[find_task(batch, &Task::search, lwg)];
+    const Shape sh = t.search;
     const uint32_t tid = threadIdx.x;
     const int radius = batch.radius;
     const bool full_search = batch.full_search != 0;
@@ -341,8 +345,8 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
 
     // tiles dealt round-robin over the tensor's workgroups (see k_absmax)
     double sse = 0.0;
-    for (uint32_t k = 0; k < t.tiles_per_wg; ++k) {
-        const uint32_t i = (k * t.n_wg + lwg) * kWG + tid;
+    for (uint32_t k = 0; k < sh.tiles_per_wg; ++k) {
+        const uint32_t i = (k * sh.n_wg + lwg) * kWG + tid;
         float w[16], q[16];
         uint32_t nib[2];
         if (kExchange && t.contiguous) {
@@ -405,12 +409,12 @@ __global__ __launch_bounds__(kWG) void k_search(const Batch batch)
     uint32_t *counters = t.counters + 2 * kSlots * kSlotStride;
     if (tid == 0) {
         publish(partS + lwg, (s_wave[0] + s_wave[1]) + (s_wave[2] + s_wave[3]));
-        s_last = arrive_is_last(counters, &t.ctrl->top[2], t.n_wg, lwg) ? 1u : 0u;
+        s_last = arrive_is_last(counters, &t.ctrl->top[2], sh.n_wg, lwg) ? 1u : 0u;
     }
     __syncthreads();
     if (!s_last) return;
     double total;
-    trees_of_partials<1>(partS, t.n_wg, s_tree, s_stack, &total);
+    trees_of_partials<1>(partS, sh.n_wg, s_tree, s_stack, &total);
     if (tid == 0) {
         if (t.sse) *t.sse = total;
         if (t.status)

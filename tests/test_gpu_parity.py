@@ -162,6 +162,22 @@ def test_search_mode_and_launch_shape_do_not_change_a_byte():
     o2 = B.quantize(w, B.SOAR_METHOD_SOAR, 8)
     torch.cuda.synchronize()
     assert o2.sse.item() == base.sse.item()
+    # the three passes with launch shapes of their own (maximum, statistics, search)
+    for method, K in ((B.SOAR_METHOD_SOAR, 8), (B.SOAR_METHOD_RTN, 0)):
+        ref = B.quantize(w, method, K, tiles_per_wg=4)
+        for a, s_, q in ((1, 4, 16), (16, 1, 2), (2, 8, 16), (4, 8, 16), (64, 2, 1), (0, 4, 4096), (8, 0, 0)):
+            p = B.soar_default_params(method, K)
+            p.tiles_per_wg, p.tiles_per_wg_absmax, p.tiles_per_wg_search = s_, a, q
+            o = B.new_outputs(spec.rows, spec.cols, DEV)
+            ws = B.new_workspace(spec.rows, spec.cols, p, DEV)
+            rc = B.soar_quantize(w.data_ptr(), B.SOAR_BF16, spec.rows, spec.cols, spec.cols, p, o.codes.data_ptr(),
+                                 o.scales.data_ptr(), o.global_scale.data_ptr(), o.sse.data_ptr(), o.status.data_ptr(),
+                                 ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+            assert rc == B.SOAR_OK
+            torch.cuda.synchronize()
+            assert torch.equal(o.codes, ref.codes) and torch.equal(o.scales, ref.scales), (method, a, s_, q)
+            assert o.global_scale.item() == ref.global_scale.item(), (method, a, s_, q)
+            assert math.isclose(o.sse.item(), ref.sse.item(), rel_tol=1e-12), (method, a, s_, q)
 
 
 def test_fp32_input_and_leading_dimension():
