@@ -148,8 +148,9 @@ typedef struct {
     int32_t  tiles_per_wg_search; /* have launch shapes of their own (the library picks them by
                                 the schedule: kernels of two launch groups share the GPU in a
                                 batch of several groups).  0 = as tiles_per_wg says, else the
-                                library's choice; a power of two <= 65536 forces that pass
-                                (tests and tuning: outputs must not depend on it)           */
+                                library's choice; 1 .. 65536 forces that pass (any count:
+                                these two deal their tiles round-robin; tests and tuning:
+                                outputs must not depend on it)                              */
 } soar_params;
 
 /* Fills *p with the single-step defaults: SOAR, block 16, T = 1, K = 4, beta = {1},

@@ -224,8 +224,10 @@ bool valid_params(const soar_params *p)
     if (p->method == SOAR_METHOD_DSS_ONLY && p->dd_mode != SOAR_DD_WINDOW) return false;
     if (p->dss_radius < 0 || p->dss_radius > 125) return false;
     if (p->search_mode != SOAR_SEARCH_AUTO && p->search_mode != SOAR_SEARCH_FULL) return false;
-    for (int32_t v : {p->tiles_per_wg, p->tiles_per_wg_absmax, p->tiles_per_wg_search})
-        if (v < 0 || v > 65536 || (v & (v - 1))) return false;
+    if (p->tiles_per_wg < 0 || p->tiles_per_wg > 65536 || (p->tiles_per_wg & (p->tiles_per_wg - 1))) return false;
+    // the maximum and the search deal their tiles round-robin: any count will do
+    if (p->tiles_per_wg_absmax < 0 || p->tiles_per_wg_absmax > 65536 || p->tiles_per_wg_search < 0 || p->tiles_per_wg_search > 65536)
+        return false;
     if (p->streams < 0 || p->streams > kLanes) return false;
     if (p->resident != SOAR_RESIDENT_AUTO && p->resident != SOAR_RESIDENT_NEVER) return false;
     if (p->resident_wait_us < 0) return false;
@@ -271,6 +273,15 @@ size_t per_block_bytes(int64_t rows, int64_t cols)
 // takes 7.26 ms instead of 8.08 (swept over 1..4 x 4..32 x 8..32: profiles/config4_launch_shape_sweep.md),
 // although the search alone is 5 % slower that way; plain NVFP4 (two passes) likes 8 in its search.
 struct WantedShapes { uint32_t absmax, stats, search; };
+
+// tiles per workgroup of an arithmetic-bound searching kernel over a launch of `tiles` tiles
+constexpr int64_t kSearchMinWg = 2048;
+uint32_t search_tiles_per_wg(int64_t tiles)
+{
+    uint32_t tpw = 16;
+    while (tpw > 1 && tiles / tpw < kSearchMinWg) tpw >>= 1;
+    return tpw;
+}
 WantedShapes wanted_shapes(bool several_groups, int method, bool iterated, bool one_pass, int64_t bytes)
 {
     if (!several_groups || iterated || one_pass) return {(uint32_t)kStage, (uint32_t)kStage, (uint32_t)kStage};
@@ -579,18 +590,28 @@ soar_status run_batch(int32_t n, const soar_tensor_desc *descs, const soar_param
         b.beta_hi = params->beta_hi;
         b.early_stop_rel = params->early_stop_rel;
         b.arm = params->method;
-        // the searching iterated kernels are arithmetic-bound: the smallest workgroups balance best
-        // (the closed-form arm has no search and streams like the single-step kernels)
+        // The searching iterated kernels are arithmetic-bound: up to 16 tiles per workgroup, as long as the launch
+        // keeps kSearchMinWg workgroups (a few rounds of what the GPU holds at once) to balance over: the
+        // full-model workload takes 267 ms per step that way, 299 with one tile per workgroup.  (The closed-form
+        // arm has no search and streams like the single-step kernels.)
         const bool searching = iterated && params->method != SOAR_METHOD_CJSO_ONLY;
-        const uint32_t tpw = params->tiles_per_wg ? (uint32_t)params->tiles_per_wg : (searching ? 1u : 0u);
+        const uint32_t tpw = (uint32_t)params->tiles_per_wg;
+        uint32_t searching_tpw = 0;
+        if (searching) {
+            int64_t group_tiles = 0;
+            for (int32_t k = i; k < j; ++k) group_tiles += (descs[k].rows * (descs[k].cols / 16) + kWG - 1) / kWG;
+            searching_tpw = search_tiles_per_wg(group_tiles);
+        }
         uint32_t wg = 0, wg_absmax = 0, wg_search = 0;
         char *per_block = lane_base + (size_t)kGroupMax * kSlotBytes;
         for (int32_t k = i; k < j; ++k) {
             const soar_tensor_desc &d = descs[k];
             const WantedShapes forced = {params->tiles_per_wg_absmax ? (uint32_t)params->tiles_per_wg_absmax : tpw, tpw,
                                          params->tiles_per_wg_search ? (uint32_t)params->tiles_per_wg_search : tpw};
-            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, forced,
-                               wanted_shapes(n_groups > 1, params->method, iterated, d.d_amax_in != nullptr, weight_bytes(d)));
+            const WantedShapes want = searching ? WantedShapes{searching_tpw, searching_tpw, searching_tpw}
+                                                : wanted_shapes(n_groups > 1, params->method, iterated, d.d_amax_in != nullptr,
+                                                                weight_bytes(d));
+            Task t = make_task(d.d_w, d.rows, d.cols, d.ld_elems, forced, want);
             t.iters_run = d.d_iters_run;
             t.trace = d.d_sse_trace;
             t.amax_in = d.d_amax_in;
@@ -993,6 +1014,8 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
         std::memset(&b, 0, sizeof(b));
         b.n = (uint32_t)(j - i);
         uint32_t wg = 0;
+        int64_t group_tiles = 0;
+        for (int32_t k = i; k < j; ++k) group_tiles += (descs[k].rows * (descs[k].cols / 32) + kWG - 1) / kWG;
         for (int32_t k = i; k < j; ++k) {
             const soar_mx_tensor_desc &d = descs[k];
             MxTask &t = b.t[k - i];
@@ -1006,8 +1029,8 @@ soar_status soar_mxfp4_quantize_batch(int32_t n, const soar_mx_tensor_desc *desc
             t.nblk = (uint32_t)(d.rows * (d.cols / 32));
             t.contiguous = d.ld_elems == d.cols ? 1u : 0u;
             const uint32_t tiles = (t.nblk + kWG - 1) / kWG;
-            // the search is arithmetic-bound (smallest workgroups balance best); the plain conversion streams
-            uint32_t tpw = params->dss ? 1u : 2u;
+            // the search is arithmetic-bound (see search_tiles_per_wg); the plain conversion streams
+            uint32_t tpw = params->dss ? search_tiles_per_wg(group_tiles) : 2u;
             while (tpw > 1 && tpw > tiles) tpw >>= 1;
             if (params->tiles_per_wg) tpw = (uint32_t)params->tiles_per_wg;
             while ((tiles + tpw - 1) / tpw > (uint32_t)kMaxPartials) tpw <<= 1;

@@ -69,7 +69,7 @@ def test_host_side_argument_validation():
     for field, bad in (("method", 7), ("block", 32), ("iters", 0), ("iters", 65), ("dss_radius", -1),
                        ("dss_radius", 200), ("n_beta", 0), ("n_beta", 4097), ("beta_lo", 0.0), ("beta_lo", 1.5),
                        ("beta_hi", float("inf")), ("early_stop_rel", -1.0), ("early_stop_rel", float("nan")),
-                       ("dd_mode", 2), ("search_mode", 9), ("tiles_per_wg", 3), ("tiles_per_wg_absmax", 6), ("tiles_per_wg_search", -2), ("streams", 3),
+                       ("dd_mode", 2), ("search_mode", 9), ("tiles_per_wg", 3), ("tiles_per_wg_absmax", 70000), ("tiles_per_wg_search", -2), ("streams", 3),
                        ("struct_size", 4)):
         q = B.soar_default_params()
         setattr(q, field, bad)

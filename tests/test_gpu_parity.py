@@ -165,7 +165,7 @@ def test_search_mode_and_launch_shape_do_not_change_a_byte():
     # the three passes with launch shapes of their own (maximum, statistics, search)
     for method, K in ((B.SOAR_METHOD_SOAR, 8), (B.SOAR_METHOD_RTN, 0)):
         ref = B.quantize(w, method, K, tiles_per_wg=4)
-        for a, s_, q in ((1, 4, 16), (16, 1, 2), (2, 8, 16), (4, 8, 16), (64, 2, 1), (0, 4, 4096), (8, 0, 0)):
+        for a, s_, q in ((1, 4, 16), (16, 1, 2), (2, 8, 16), (4, 8, 16), (64, 2, 1), (0, 4, 4096), (8, 0, 0), (3, 8, 14), (5, 2, 23)):
             p = B.soar_default_params(method, K)
             p.tiles_per_wg, p.tiles_per_wg_absmax, p.tiles_per_wg_search = s_, a, q
             o = B.new_outputs(spec.rows, spec.cols, DEV)
