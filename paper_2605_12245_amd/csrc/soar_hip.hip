@@ -708,6 +708,16 @@ soar_status run_stored_batch(int32_t n, const soar_stored_desc *descs, bool reco
         soar_status s = validate_stored(descs[k], recon);
         if (s != SOAR_OK) return s;
     }
+    if (recon) {
+        // all sums of the call first, kZeroMax per launch
+        for (int32_t i = 0; i < n; i += kZeroMax) {
+            ZeroBatch z;
+            z.n = (uint32_t)(n - i < kZeroMax ? n - i : kZeroMax);
+            for (uint32_t k = 0; k < z.n; ++k) z.sum[k] = descs[i + (int32_t)k].d_sse;
+            hipLaunchKernelGGL(k_zero_sums, dim3(1), dim3(kZeroMax), 0, st, z);
+            SOAR_LAUNCH_CHECK();
+        }
+    }
     for (int32_t i = 0; i < n;) {
         const int32_t j = stored_group_end(n, descs, i);
         StoredBatch b;
@@ -732,8 +742,6 @@ soar_status run_stored_batch(int32_t n, const soar_stored_desc *descs, bool reco
         const bool bf16 = descs[i].dtype == SOAR_BF16;
         ScopedTimer tm(recon ? SOAR_KERNEL_RECON : SOAR_KERNEL_DEQUANT, st);
         if (recon) {
-            hipLaunchKernelGGL(k_zero_sums, dim3(1), dim3(64), 0, st, b);
-            SOAR_LAUNCH_CHECK();
             if (bf16) hipLaunchKernelGGL(k_recon<SOAR_BF16>, dim3(wg), dim3(kReconWG), 0, st, b);
             else hipLaunchKernelGGL(k_recon<SOAR_FP32>, dim3(wg), dim3(kReconWG), 0, st, b);
         } else {

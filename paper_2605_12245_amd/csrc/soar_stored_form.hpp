@@ -150,10 +150,17 @@ __global__ __launch_bounds__(kWG) void k_mx_dequant(const StoredBatch batch)
     }
 }
 
-// clears the sums of a launch of k_recon (a kernel, not a memset: the call may be captured into a graph)
-__global__ void k_zero_sums(const StoredBatch batch)
+// clears the sums of a call of k_recon launches (a kernel, not a memset: the call may be captured into a graph);
+// one launch for up to kZeroMax tensors, whose addresses travel in the kernel arguments
+constexpr int kZeroMax = 448;
+struct ZeroBatch {
+    double *sum[kZeroMax];
+    uint32_t n;
+};
+static_assert(sizeof(ZeroBatch) <= 4096, "kernel arguments");
+__global__ __launch_bounds__(kZeroMax) void k_zero_sums(const ZeroBatch batch)
 {
-    if (threadIdx.x < batch.n) *batch.t[threadIdx.x].sse = 0.0;
+    if (threadIdx.x < batch.n) *batch.sum[threadIdx.x] = 0.0;
 }
 
 // Eq. 4 for stored codes and scales.  Every workgroup ends with one binary64 atomic addition to its
