@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kZeroMax) void k_zero_sums(const ZeroBatch batch)
 // more than the reads of a whole tensor), so the workgroups are few and large: 16 waves each, at most
 // kReconGrid per tensor.
 constexpr int kReconWG = 1024;
-constexpr uint32_t kReconGrid = 512;
+constexpr uint32_t kReconGrid = 256;      // 512: 5 % slower on the full-model workload, 8 % on 448 MiB tensors; 64-128: as 256
 template <int DT>
 __global__ __launch_bounds__(kReconWG) void k_recon(const StoredBatch batch)
 {
