@@ -208,8 +208,10 @@ size_t soar_workspace_bytes(int64_t rows, int64_t cols, const soar_params *param
  * d_sse          out  1 double, may be NULL: sum over blocks of the Eq. 8 error
  *                     of the emitted codes and scales (= Eq. 4).  The order of the
  *                     binary64 additions follows the launch shape: bit-identical
- *                     from call to call for a fixed tiles_per_wg and path (one
- *                     launch / three passes), equal to within 1e-12 otherwise
+ *                     from call to call for the same call (same tiles_per_wg*
+ *                     settings, same path: one launch / three passes, same
+ *                     tensors in a batch: the library picks the shapes by the
+ *                     number of launch groups), equal to within 1e-12 otherwise
  * d_status       out  1 int32, may be NULL: SOAR_STATUS_* bits
  * d_workspace    tmp  >= soar_workspace_bytes(), 256-byte aligned; calls that
  *                     share a workspace must be ordered on one stream
