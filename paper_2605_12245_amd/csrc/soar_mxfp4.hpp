@@ -229,7 +229,7 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
     __shared__ double s_tree[kWG];
     __shared__ uint32_t s_last;
     constexpr int kP = pieces_per_block<DT, 32>();
-    __shared__ u32x4 s_x[DSS ? 1 : kWG * kP];          // load_wave_blocks: one region per wave
+    __shared__ u32x4 s_x[(DSS || DT != SOAR_BF16) ? 1 : kWG * kP];   // load_wave_blocks: one region per wave
     // dynamic LDS: the factor table (rounded up to 256 bytes), then the change lists of the two-pass search
     extern __shared__ __align__(16) unsigned char s_dyn_mx[];
     float *s_beta = reinterpret_cast<float *>(s_dyn_mx);
@@ -255,8 +255,8 @@ __global__ __launch_bounds__(kWG) void k_mx(const MxBatch batch)
         double term[1] = {0.0};
         float w[32];
         // the plain conversion is bound by the reads: packed rows go through the coalescing exchange
-        const bool exchanged = !DSS && t.contiguous;
-        if constexpr (!DSS) {
+        const bool exchanged = !DSS && DT == SOAR_BF16 && t.contiguous;
+        if constexpr (!DSS && DT == SOAR_BF16) {
             if (exchanged) load_wave_blocks<DT, 32, true>(t.w, i - (tid & 63u), t.nblk, s_x + (tid >> 6) * (64 * kP), w);
         }
         if (i < t.nblk) {
