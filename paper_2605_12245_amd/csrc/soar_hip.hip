@@ -273,6 +273,14 @@ size_t per_block_bytes(int64_t rows, int64_t cols)
 // takes 7.26 ms instead of 8.08 (swept over 1..4 x 4..32 x 8..32: profiles/config4_launch_shape_sweep.md),
 // although the search alone is 5 % slower that way; plain NVFP4 (two passes) likes 8 in its search.
 struct WantedShapes { uint32_t absmax, stats, search; };
+WantedShapes wanted_shapes(bool several_groups, int method, bool iterated, bool one_pass, int64_t bytes)
+{
+    if (!several_groups || iterated || one_pass) return {(uint32_t)kStage, (uint32_t)kStage, (uint32_t)kStage};
+    // a tensor that is a launch group by itself and larger than the last-level cache streams from HBM in every
+    // pass; plain NVFP4 has two passes only
+    if (method == SOAR_METHOD_RTN || bytes > kGroupByteCap) return {(uint32_t)kStage, (uint32_t)kStage, 8u};
+    return {(uint32_t)kStage, 8u, 16u};
+}
 
 // tiles per workgroup of an arithmetic-bound searching kernel over a launch of `tiles` tiles
 constexpr int64_t kSearchMinWg = 2048;
@@ -281,14 +289,6 @@ uint32_t search_tiles_per_wg(int64_t tiles)
     uint32_t tpw = 16;
     while (tpw > 1 && tiles / tpw < kSearchMinWg) tpw >>= 1;
     return tpw;
-}
-WantedShapes wanted_shapes(bool several_groups, int method, bool iterated, bool one_pass, int64_t bytes)
-{
-    if (!several_groups || iterated || one_pass) return {(uint32_t)kStage, (uint32_t)kStage, (uint32_t)kStage};
-    // a tensor that is a launch group by itself and larger than the last-level cache streams from HBM in every
-    // pass; plain NVFP4 has two passes only
-    if (method == SOAR_METHOD_RTN || bytes > kGroupByteCap) return {(uint32_t)kStage, (uint32_t)kStage, 8u};
-    return {(uint32_t)kStage, 8u, 16u};
 }
 
 // addressing and launch shapes of one tensor; the workspace fields and the first workgroups stay unset
